@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the ECO optimizer step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+
+A "step" is one eco_step call over the whole synthetic parameter set (dequantize, Adam update without
+master weights, abs-max re-quantization with stochastic rounding, error injection into momentum), with
+all inputs resident in HBM.  Fresh bf16 gradients are drawn on the device before every step, outside
+the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "ECO optimizer-step params/sec and achieved HBM GB/s (% of peak), 1 GPU"
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
+
+# Algorithmic bytes per parameter the method must move in one step (read + write):
+#   FP8 codes 1+1, fp32 scale per 128 elements (4+4)/128, bf16 gradient 2, fp32 m 4+4, fp32 v 4+4
+BYTES_PER_PARAM = {"fp8": 20.0625, "int4": 11.03125, "bf16_plain": 22.0}
+
+
+def algorithmic_bytes(wl) -> float:
+    total = 0.0
+    for t in wl.tensors:
+        if t.fmt == "fp8":
+            sb = 2 if wl.scale_bf16 else 4
+            st = 2 if wl.state_bf16 else 4
+            total += t.numel * (2 * 1 + 2 + 4 * st + 2 * sb / wl.block_size)
+        elif t.fmt == "int4":
+            sb = 2 if wl.scale_bf16 else 4
+            st = 2 if wl.state_bf16 else 4
+            total += t.numel * (2 * 0.5 + 2 + 4 * st + 2 * sb / wl.block_size)
+        else:
+            st = 2 if wl.state_bf16 else 4
+            total += t.numel * (2 * 2 + 2 + 4 * st)
+    return total
+
+
+def cpu_baseline(wl, target_seconds: float = 12.0) -> dict:
+    """The CPU oracle, as it stands, timed on a bounded sample of the same workload (host cores of this machine)."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    o = oracle.get("f32")
+    fmt_map = {"fp8": oracle.FMT_E4M3, "int4": oracle.FMT_INT4}
+    quant = [i for i, t in enumerate(wl.tensors) if t.fmt in fmt_map]
+
+    def prepare(ids):
+        items = []
+        for i in ids:
+            t = wl.tensors[i]
+            w = workloads.initial_weights(wl, i, "cpu").numpy()
+            codes, scales = o.quantize_rtn(fmt_map[t.fmt], w, wl.block_size, wl.scale_bf16)
+            g = workloads.gradient(wl, i, 1, "cpu")
+            import torch
+            g16 = g.view(torch.int16).numpy().view(np.uint16).copy()
+            items.append((i, t, codes, scales, g16, np.zeros(t.numel, np.float32), np.zeros(t.numel, np.float32)))
+        return items
+
+    def run(items):
+        n = 0
+        t0 = time.perf_counter()
+        for i, t, codes, scales, g16, m, v in items:
+            cfg = oracle.StepConfig(fmt=fmt_map[t.fmt], block_size=wl.block_size, state_bf16=wl.state_bf16,
+                                    scale_bf16=wl.scale_bf16, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
+                                    step=1, seed=workloads.BASE_SEED, tensor_id=i)
+            assert o.eco_step(cfg, t.numel, m, v, codes=codes, scales=scales, grad_bf16=g16) == 0
+            n += t.numel
+        return n, time.perf_counter() - t0
+
+    # probe with the first tensor(s) up to ~2M parameters, then size the sample for the time target
+    probe_ids, acc = [], 0
+    for i in quant:
+        probe_ids.append(i)
+        acc += wl.tensors[i].numel
+        if acc >= 2_000_000:
+            break
+    n0, dt0 = run(prepare(probe_ids))
+    rate = n0 / dt0
+    want = rate * target_seconds
+    ids, acc = [], 0
+    for i in quant:
+        if acc >= want and ids:
+            break
+        if acc + wl.tensors[i].numel > 4 * want and ids:
+            continue
+        ids.append(i)
+        acc += wl.tensors[i].numel
+    n, dt = run(prepare(ids))
+    return {"value": n / dt, "unit": "params/s", "cores": o.num_threads(), "kind": "oracle",
+            "sample": f"one step over the first {len(ids)} quantized tensors of the workload ({n} parameters), "
+                      f"fp32 build of the oracle, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="workload number (1-5) of the baseline's configs")
+    ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning: workgroups per compute unit (0 = default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build measures the ECO step on ONE GPU only (the step shards over blocks with no "
+              "exchange; multi-GPU runs are not part of it). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import workloads
+    from paper_2601_22101_amd import binding as eco
+    from paper_2601_22101_amd import harness
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    if args.wgs_per_cu:
+        eco.eco_set_option(0, args.wgs_per_cu)
+
+    wl = workloads.CONFIGS[args.config]()
+    t_setup = time.perf_counter()
+    dw = harness.DeviceWorkload(wl, "cuda:0")
+    torch.cuda.synchronize()
+    print(f"[bench] {wl.name}: {len(wl.tensors)} tensors, {wl.numel} parameters, set-up {time.perf_counter() - t_setup:.1f} s",
+          file=sys.stderr, flush=True)
+
+    k = 0
+    for _ in range(args.warmup):
+        k += 1
+        dw.fill_gradients(k)
+        dw.step(k)
+    torch.cuda.synchronize()
+
+    wall, kernel_ms = 0.0, []
+    for _ in range(args.steps):
+        k += 1
+        dw.fill_gradients(k)                      # fresh gradients, outside the timed region
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        dw.step(k)
+        e1.record()
+        torch.cuda.synchronize()
+        wall += time.perf_counter() - t0
+        kernel_ms.append(e0.elapsed_time(e1))
+        print(f"[bench] step {k}: {kernel_ms[-1]:.3f} ms", file=sys.stderr, flush=True)
+
+    ms_per_step = wall / args.steps * 1e3
+    value = wl.numel / (ms_per_step * 1e-3)
+    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) * 1e-3
+    alg_bytes = algorithmic_bytes(wl)
+    achieved = alg_bytes / avg_kernel_s / 1e9
+    out = {
+        "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "tensors": len(wl.tensors), "parameters": wl.numel,
+                   "format": "fp8_e4m3 codes, block-128 fp32 scales, bf16 gradients, fp32 m and v"
+                   if args.config != 5 else "int4 codes, group-128 bf16 scales, bf16 gradients, bf16 m and v",
+                   "optimizer": "Adam-ECO, stochastic rounding", "launches_per_step": 1 if args.config != 2 else 2},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": avg_kernel_s * 1e3},
+    }
+    dw.close()
+    del dw
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,185 @@
+/*
+ * eco.h — C ABI of the ECO optimizer-step library for AMD MI355X (gfx950).
+ *
+ * ECO ("Error-Compensating Optimizer", paper "ECO: Quantized Training without
+ * Full-Precision Master Weights") trains with quantized weights and no
+ * high-precision master copy: each step applies the optimizer update directly
+ * to the de-quantized weights, re-quantizes, and adds the quantization error,
+ * suitably scaled, to the first-moment buffer (Alg. 1: OPTIM_STEP followed by
+ * ECO_QUANTIZE; Alg. 2 for SGD with momentum, Alg. 3 for Adam).
+ *
+ * One call of eco_step() performs, for every scale group ("block") of
+ * `block_size` consecutive elements of every tensor of a plan, in one fused
+ * pass over memory:
+ *     theta^  = dec(code) * scale                         (Sec. 3.1, x^ = s*y)
+ *     m~ = b1*m + (1-b1)*g ;  v~ = b2*v + (1-b2)*g*g      (Sec. 3.2 / Eq. m_tilde)
+ *     d  = sqrt(v~/(1-b2^k)) + eps
+ *     theta~ = theta^ - (lr/(1-b1^k)) * m~ / d            (Sec. 3.2, Adam display eq.)
+ *     scale' = max|theta~| / rho ;  code' = round(theta~ * rho/max|theta~|)
+ *                                                         (Sec. 3.1, Eq. 1 and s = max|x|/rho)
+ *     e  = theta~ - dec(code')*scale'                     (Alg. 3 line 2)
+ *     m^ = m~ + ((1-b1^k)/lr)(1-1/b1) * d * e             (Alg. 3 line 5);  v^ = v~
+ * with `round` either round-to-nearest-even or stochastic rounding driven by a
+ * counter-based Philox4x32-10 generator.  For SGD with momentum:
+ *     m~ = b*m + (1-b)*g ; theta~ = theta^ - lr*m~ ; m^ = m~ + (1/lr)(1-1/b)*e
+ *                                                         (Sec. 3.3.1 Eqs. m_tilde..alpha, Alg. 2)
+ *
+ * Conventions
+ *  - Every data pointer in eco_tensor_t and in the helper calls is a DEVICE
+ *    pointer owned by the caller; descriptors and hyper-parameter structs are
+ *    HOST memory and are read during the call only.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *    work is enqueued on it; no call synchronizes unless it says so.
+ *  - Weights, scales, m and v are updated in place; gradients are only read.
+ *  - Every function returns an eco_status_t; nothing aborts or throws.  After a
+ *    failure eco_last_error() (thread-local) describes it, and no kernel of
+ *    that call has been launched unless the status is ECO_EHIP.
+ *  - Results depend only on the inputs, the hyper-parameters, (seed, step,
+ *    tensor_id) and the element index: never on launch geometry, on the order
+ *    of tensors in a plan, or on which tensors share a launch.
+ *  - Inputs are assumed finite; behaviour on NaN/Inf is unspecified.
+ *  - A plan may be used by one host thread at a time.
+ */
+#ifndef ECO_H
+#define ECO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ECO_OK = 0,
+  ECO_EINVAL = -1,        /* null pointer, zero size, step == 0, lr/beta out of range, ... */
+  ECO_EALIGN = -2,        /* a data pointer is not 16-byte aligned                          */
+  ECO_EUNSUPPORTED = -3,  /* no kernel for this combination (e.g. block size)               */
+  ECO_EHIP = -4,          /* a HIP runtime call failed (no device, launch error, ...)       */
+  ECO_ENOMEM = -5         /* host or device allocation for a plan failed                    */
+} eco_status_t;
+
+/* Storage format of a tensor's weights (Sec. 3.1: the format fixes rho and the code grid). */
+typedef enum {
+  ECO_FMT_FP8_E4M3 = 0,      /* 1 byte/element, OCP E4M3 (bias 7, max 448, S.1111.111 = NaN, no Inf); rho = 448 */
+  ECO_FMT_INT4 = 1,          /* 2 elements/byte, two's complement in [-7,7], element 2j in the low nibble; rho = 7 */
+  ECO_FMT_BF16_PLAIN = 2,    /* bfloat16 weights, no quantizer and no injection: ordinary Adam/SGDM (the paper
+                                applies the method to linear layers only, Sec. 4.2 "Setting")                      */
+  ECO_FMT_FP32_IDENTITY = 3  /* fp32 weights, identity quantizer: e = 0, the step reduces to the plain optimizer   */
+} eco_format_t;
+
+typedef enum { ECO_OPT_ADAM = 0, ECO_OPT_SGDM = 1 } eco_opt_t;       /* Alg. 3 / Alg. 2              */
+typedef enum { ECO_ROUND_SR = 0, ECO_ROUND_RTN = 1 } eco_round_t;    /* Sec. 3.1, rounding function  */
+typedef enum { ECO_DT_FP32 = 0, ECO_DT_BF16 = 1 } eco_dtype_t;
+
+/* One parameter tensor, flattened row-major.  Element i belongs to scale group i / block_size;
+ * the last group may be shorter.  All pointers: device memory, 16-byte aligned. */
+typedef struct eco_tensor {
+  void *weights;        /* FP8: numel bytes; INT4: ceil(numel/2) bytes; BF16_PLAIN: numel bf16; FP32_IDENTITY: numel fp32 */
+  void *scales;         /* ceil(numel/block_size) entries of scale_dtype; ignored (may be NULL) for the last two formats  */
+  const void *grad;     /* numel bfloat16, read only                                                                       */
+  void *m;              /* first moment, numel entries of state_dtype                                                      */
+  void *v;              /* second moment, numel entries of state_dtype; ignored (may be NULL) for ECO_OPT_SGDM             */
+  uint64_t numel;       /* > 0                                                                                             */
+  uint32_t tensor_id;   /* enters the random-number counter; keep it stable across steps and distinct across tensors      */
+  int32_t fmt;          /* eco_format_t                                                                                    */
+} eco_tensor_t;
+
+/* Hyper-parameters H of Alg. 1-3 plus the description of the quantizer and of the state layout. */
+typedef struct eco_hparams {
+  int32_t opt;            /* eco_opt_t                                                                     */
+  int32_t round;          /* eco_round_t: rounding used when re-quantizing                                 */
+  int32_t inject;         /* 1: ECO (inject the error into m); 0: naive master-weight removal, m^ = m~     */
+  uint32_t block_size;    /* elements per scale group: 32, 64, 128, 256 or 512                             */
+  int32_t state_dtype;    /* eco_dtype_t of m and v (math is fp32; bf16 state is rounded to nearest even)  */
+  int32_t scale_dtype;    /* eco_dtype_t of the scales                                                     */
+  double lr;              /* eta  (> 0 when inject)                                                        */
+  double beta1;           /* beta1, or beta for SGDM (in (0,1) when inject: the injection divides by it)   */
+  double beta2;           /* beta2 (Adam only, in [0,1))                                                   */
+  double eps;             /* epsilon (Adam only, >= 0)                                                     */
+  double weight_decay;    /* decoupled decay lambda: theta^ <- theta^ - lr*lambda*theta^ before the update */
+  uint64_t step;          /* k >= 1: the 1-based index of the step being taken (bias corrections 1-beta^k) */
+  uint64_t seed;          /* key of the stochastic-rounding generator                                      */
+} eco_hparams_t;
+
+/* The fp32 constants a step uses, derived from eco_hparams_t in double and rounded once. */
+typedef struct eco_constants {
+  float b1, omb1, b2, omb2;   /* beta1, 1-beta1, beta2, 1-beta2                     */
+  float rbc2;                 /* 1/(1-beta2^k)                                       */
+  float c1;                   /* lr/(1-beta1^k)  (Adam);                             */
+  float eps;
+  float kappa;                /* ((1-beta1^k)/lr)(1-1/beta1)  (Alg. 3 line 5); 0 if !inject */
+  float lr;                   /* eta (SGDM)                                          */
+  float alpha;                /* (1/lr)(1-1/beta)  (Eq. alpha); 0 if !inject         */
+  float wd;                   /* lr*lambda                                           */
+  float reserved;
+} eco_constants_t;
+
+typedef struct eco_plan eco_plan_t;
+
+/*
+ * eco_plan_create — validate a list of tensors and upload its launch tables (Alg. 1 is applied to
+ * every tensor of the list by one eco_step call; tensors of different formats may be mixed).
+ *   tensors, n : HOST array of n >= 1 descriptors (copied; may be freed after the call)
+ *   layout     : HOST; only block_size, state_dtype, scale_dtype and opt are read (they fix the memory
+ *                layout the descriptors are checked against)
+ *   out        : receives the plan; owned by the library until eco_plan_destroy
+ * Allocates device memory for the tables (about 64 bytes per tensor + 4 bytes per 2048 elements) and
+ * copies them synchronously.  Errors: ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_ENOMEM, ECO_EHIP.
+ */
+eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *layout, eco_plan_t **out);
+
+/* Frees the plan's host and device tables (synchronizes the device first).  NULL is allowed. */
+eco_status_t eco_plan_destroy(eco_plan_t *plan);
+
+/*
+ * eco_step — one ECO step (Alg. 1 with Alg. 3 or Alg. 2) over every tensor of the plan.
+ * Asynchronous on `stream`; allocates nothing; one kernel launch per storage format present.
+ * hp->block_size, state_dtype, scale_dtype and opt must equal the plan's.
+ */
+eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream);
+
+/*
+ * eco_step_tensors — convenience form without a persistent plan: builds the tables, runs the step,
+ * waits for `stream`, and frees the tables.  Allocates device memory and synchronizes.
+ */
+eco_status_t eco_step_tensors(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *hp, void *stream);
+
+/*
+ * eco_quantize_init — q(x) of Sec. 3.1 with round-to-nearest-even, for setting up quantized weights.
+ *   src    : device, numel values of src_dtype (ECO_DT_FP32 or ECO_DT_BF16)
+ *   weights, scales : device outputs, laid out as in eco_tensor_t
+ * fmt must be ECO_FMT_FP8_E4M3 or ECO_FMT_INT4.  Asynchronous on `stream`.
+ */
+eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint32_t block_size,
+                               int32_t scale_dtype, void *weights, void *scales, void *stream);
+
+/* eco_dequantize — dst[i] = dec(code_i) * scale[i / block_size] as fp32 (Sec. 3.1, x^ = s*y).  Asynchronous. */
+eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint32_t block_size,
+                            int32_t scale_dtype, float *dst, void *stream);
+
+/*
+ * eco_philox_fill — the raw random stream the stochastic rounding of (seed, step, tensor_id) draws from:
+ * dst[j] = output word (j & 3) of Philox4x32-10 with key (seed lo, seed hi) and counter
+ * ((j>>2) lo, (j>>2) hi, step lo, tensor_id), for j = first_word .. first_word + n_words - 1.
+ * Element i of a tensor uses bits 16*(i&1) .. 16*(i&1)+15 of word (i>>3)*4 + ((i&7)>>1).
+ * dst: device, n_words uint32.  Asynchronous.
+ */
+eco_status_t eco_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_word, uint64_t n_words,
+                             uint32_t *dst, void *stream);
+
+/* eco_step_constants — host only: validates hp as eco_step does and writes the derived fp32 constants. */
+eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out);
+
+/* Launch tuning, host only.  option 0: workgroups per compute unit of the persistent step kernel
+ * (0 = library default).  Does not change results. */
+eco_status_t eco_set_option(int32_t option, int64_t value);
+
+const char *eco_status_string(eco_status_t status);
+const char *eco_last_error(void);   /* thread-local, never NULL */
+int eco_version(void);              /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECO_H */

@@ -1,0 +1,138 @@
+// Device-side building blocks of the ECO step for gfx950 (wave64): number formats, the
+// Philox4x32-10 generator, the grid encoders (stochastic and nearest-even rounding) and the
+// in-wave abs-max reduction.  Everything here is exact integer or single-operation IEEE fp32
+// arithmetic, so results are reproducible bit for bit on any conforming implementation.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace eco {
+
+enum : int { FMT_FP8 = 0, FMT_INT4 = 1, FMT_BF16_PLAIN = 2, FMT_FP32_ID = 3 };
+enum : int { OPT_ADAM = 0, OPT_SGDM = 1 };
+enum : int { ROUND_SR = 0, ROUND_RTN = 1 };
+
+__device__ __forceinline__ uint32_t f2u(float x) { return __float_as_uint(x); }
+__device__ __forceinline__ float u2f(uint32_t x) { return __uint_as_float(x); }
+
+// ---------------------------------------------------------------------------------- bfloat16
+// A bfloat16 is the upper half of an fp32.
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return u2f(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return u2f(packed & 0xFFFF0000u); }
+
+// fp32 -> bfloat16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
+  uint32_t u = f2u(x);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// ---------------------------------------------------------------------------------- E4M3 (OCP)
+// Decode byte `sel` of a dword holding four codes.  Code c = S.EEEE.MMM; (c & 0x7F) << 20 placed
+// in an fp32 has exponent field E and the mantissa's top bits MMM, i.e. the value
+// 2^(E-127) * (1 + M/8) for E >= 1 and the fp32 subnormal M * 2^-129 for E = 0; multiplying by
+// 2^120 gives 2^(E-7)(1+M/8) resp. M * 2^-9, which is the E4M3 value.  The product is exact.
+template <int SEL>
+__device__ __forceinline__ float e4m3_decode(uint32_t packed) {
+#if defined(ECO_HW_FP8_DECODE)
+  return __builtin_amdgcn_cvt_f32_fp8((int)packed, SEL);
+#else
+  const uint32_t c = (packed >> (8 * SEL)) & 0xFFu;
+  const float mag = u2f((c & 0x7Fu) << 20) * 0x1p120f;
+  return u2f(f2u(mag) | ((c & 0x80u) << 24));
+#endif
+}
+
+// Position of |y| on the E4M3 code axis, in units of 2^-20 codes: codes are linear in the fp32
+// bit pattern above 2^-6 (three mantissa bits kept, twenty dropped) and linear in the value
+// below it (spacing 2^-9), where the fp32 addition of 2^-6 performs the round-to-nearest-even
+// onto multiples of 2^-29.
+constexpr uint32_t E4M3_MIN_NORMAL_BITS = 0x3C800000u;     // fp32 bit pattern of 2^-6
+
+// NORMAL_ONLY: the caller guarantees |y| >= 2^-6 (the common case, decided once per wave).
+template <int ROUND, bool NORMAL_ONLY>
+__device__ __forceinline__ uint32_t e4m3_encode(float y, uint32_t r16) {
+  const uint32_t b = f2u(y) & 0x7FFFFFFFu;
+  uint32_t mag;
+  if (ROUND == ROUND_SR) {
+    uint32_t axis = b - 0x3C000000u;                        // code 8 <-> 0x3C800000
+    if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = f2u(u2f(b) + 0x1p-6f) - 0x3C800000u;
+    mag = (axis + (r16 << 4)) >> 20;                        // up iff frac20 + 16*r16 >= 2^20
+  } else {
+    if (NORMAL_ONLY || b >= E4M3_MIN_NORMAL_BITS) {
+      const uint32_t k = b - 0x3C000000u;
+      mag = (k + 0x7FFFFu + ((k >> 20) & 1u)) >> 20;        // nearest, ties to the even code
+    } else {
+      mag = f2u(u2f(b) + 0x1p14f) - 0x46800000u;            // ulp(2^14) = 2^-9: exact nearest-even
+    }
+  }
+  mag = mag < 126u ? mag : 126u;                            // saturate at 448 (0x7E)
+  return mag | ((f2u(y) >> 24) & 0x80u);
+}
+
+// ---------------------------------------------------------------------------------- INT4
+__device__ __forceinline__ float int4_decode(uint32_t packed, int idx) {
+  const int v = ((int)(packed << (28 - 4 * idx))) >> 28;    // sign-extended nibble
+  return (float)v;
+}
+
+template <int ROUND>
+__device__ __forceinline__ uint32_t int4_encode(float y, uint32_t r16) {
+  const float ay = u2f(f2u(y) & 0x7FFFFFFFu);
+  uint32_t mag;
+  if (ROUND == ROUND_SR) {
+    // ulp(8.0) = 2^-20: the addition rounds |y| to nearest-even multiples of 2^-20
+    // (for |y| >= 8 the bit pattern keeps growing, so the result saturates below)
+    const uint32_t k = f2u(ay + 8.0f) - 0x41000000u;
+    mag = (k + (r16 << 4)) >> 20;
+  } else {
+    mag = f2u(ay + 0x1p23f) - 0x4B000000u;                  // ulp(2^23) = 1: exact nearest-even
+  }
+  mag = mag < 7u ? mag : 7u;
+  const uint32_t neg = f2u(y) >> 31;
+  return (neg ? (0u - mag) : mag) & 15u;
+}
+
+// ---------------------------------------------------------------------------------- Philox4x32-10
+// Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11).
+struct Philox4 { uint32_t w0, w1, w2, w3; };
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return Philox4{c0, c1, c2, c3};
+}
+
+// ---------------------------------------------------------------------------------- abs-max
+// All-reduce max over groups of `lanes` consecutive lanes (4, 8, 16, 32 or 64; wave-uniform) of
+// the bit patterns of non-negative floats (for which unsigned integer order is float order): DPP
+// row operations inside a 16-lane row, LDS-crossbar swizzles across rows.  max is exact and order
+// independent, so every lane of a group ends with the same bits.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_umax(uint32_t x) {
+  const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+  return x > o ? x : o;
+}
+
+__device__ __forceinline__ uint32_t group_umax(uint32_t x, int lanes) {
+  x = dpp_umax<0xB1>(x);                    // quad_perm [1,0,3,2]
+  x = dpp_umax<0x4E>(x);                    // quad_perm [2,3,0,1]
+  if (lanes >= 8) x = dpp_umax<0x141>(x);   // row_half_mirror
+  if (lanes >= 16) x = dpp_umax<0x140>(x);  // row_mirror
+  if (lanes >= 32) { const uint32_t o = (uint32_t)__shfl_xor((int)x, 16, 64); x = x > o ? x : o; }
+  if (lanes >= 64) { const uint32_t o = (uint32_t)__shfl_xor((int)x, 32, 64); x = x > o ? x : o; }
+  return x;
+}
+
+}  // namespace eco

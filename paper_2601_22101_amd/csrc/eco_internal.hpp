@@ -1,0 +1,61 @@
+// Host/device shared declarations of the ECO library: launch tables and launcher entry points.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+namespace eco {
+
+// A tile is TILE_ELEMS consecutive elements of one tensor; a 256-thread workgroup processes one
+// tile per loop iteration, 8 consecutive elements per lane.  A scale group of B elements
+// therefore occupies B/8 consecutive lanes (B = 32..512 fits inside one 64-lane wave).
+constexpr int TILE_ELEMS = 2048;
+constexpr int WG_THREADS = 256;
+constexpr int ELEMS_PER_LANE = 8;
+
+struct TensorDesc {          // 64 bytes, device table entry
+  void *w;                   // weights / codes
+  void *s;                   // scales
+  const void *g;             // bf16 gradient
+  void *m;
+  void *v;
+  uint64_t numel;
+  uint32_t first_tile;       // index of this tensor's first tile in the group's tile list
+  uint32_t tensor_id;
+  uint64_t pad;
+};
+static_assert(sizeof(TensorDesc) == 64, "TensorDesc layout");
+
+struct StepArgs {            // by-value kernel argument: everything wave-uniform
+  const TensorDesc *tensors;
+  const uint32_t *tile_tensor;   // tile -> index into tensors
+  uint32_t num_tiles;
+  uint32_t bs_shift;             // log2(block_size)
+  float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd;
+  uint32_t seed_lo, seed_hi, step_lo;
+};
+
+struct KernelVariant {
+  int fmt;          // FMT_*
+  int state_bf16;   // m, v stored as bfloat16
+  int scale_bf16;
+  int opt;          // OPT_*
+  int round;        // ROUND_*
+};
+
+// Each launcher enqueues one kernel on `stream` and returns hipGetLastError().
+hipError_t launch_step(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream);
+hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, int fmt, uint32_t bs_shift,
+                                int scale_bf16, void *weights, void *scales, unsigned grid, hipStream_t stream);
+hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint32_t bs_shift,
+                             int scale_bf16, float *dst, unsigned grid, hipStream_t stream);
+hipError_t launch_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_word, uint64_t n_words,
+                              uint32_t *dst, hipStream_t stream);
+
+// per-(fmt, state) translation units of the quantized step kernel
+hipError_t launch_step_fp8_f32(const KernelVariant &, const StepArgs &, unsigned, hipStream_t);
+hipError_t launch_step_fp8_bf16(const KernelVariant &, const StepArgs &, unsigned, hipStream_t);
+hipError_t launch_step_int4_f32(const KernelVariant &, const StepArgs &, unsigned, hipStream_t);
+hipError_t launch_step_int4_bf16(const KernelVariant &, const StepArgs &, unsigned, hipStream_t);
+hipError_t launch_step_plain(const KernelVariant &, const StepArgs &, unsigned, hipStream_t);
+
+}  // namespace eco

@@ -1,0 +1,328 @@
+// The fused ECO step kernel for quantized tensors (FP8-E4M3 or INT4 codes with per-block scales).
+//
+// One pass over memory per step: every lane owns 8 consecutive elements, loads their codes,
+// gradient and optimizer state, de-quantizes, applies the optimizer update (Alg. 1 line 1 with
+// the Adam form of Sec. 3.2, or the SGDM recurrences of Sec. 3.3.1), reduces the block's abs-max
+// across the B/8 lanes that share a scale (Sec. 3.1, s = max|x|/rho), re-quantizes with
+// stochastic or nearest-even rounding, forms the quantization error and injects it into the
+// first moment (Alg. 3 line 5 / Alg. 2 line 5), and stores codes, scale, m and v.
+//
+// The arithmetic is a fixed sequence of single IEEE fp32 operations (the build disables
+// contraction; fused multiply-adds are explicit), so that the codes and scales it produces can
+// be reproduced bit for bit elsewhere:
+//   w  = dec(code) * s_old            g = f32(bf16 gradient)
+//   m~ = fma(b1, m, omb1*g)           v~ = fma(b2, v, omb2*(g*g))
+//   d  = sqrt(v~ * rbc2) + eps        u  = (c1 * m~) / d         [SGDM: u = lr * m~]
+//   theta~ = w - u                    [with decay: (w - wd*w) - u]
+//   a = max|theta~| over the block;   s' = a / rho;  inv = rho / a
+//       [bf16 scales: s' = bf16(a/rho), inv = 1/s'];  if inv is not finite: s' = inv = 0
+//   y = theta~ * inv;  code' = round(y);  q = dec(code') * s';  e = theta~ - q
+//   m^ = fma(kappa*d, e, m~)          [SGDM: fma(alpha, e, m~)]
+#pragma once
+#include "eco_device.hpp"
+#include "eco_internal.hpp"
+
+namespace eco {
+
+template <int FMT> struct FmtTraits;
+template <> struct FmtTraits<FMT_FP8> { static constexpr float RHO = 448.0f; };
+template <> struct FmtTraits<FMT_INT4> { static constexpr float RHO = 7.0f; };
+
+// ------------------------------------------------------------------ 8-element loads and stores
+// FULL: all 8 elements exist (vector access).  Otherwise only the first `nvalid` (possibly <= 0)
+// exist: element-wise access, missing elements read as zero and are not written.
+
+template <bool FULL>
+__device__ __forceinline__ void load_f32x8(const float *p, int nvalid, float (&out)[8]) {
+  if (FULL) {
+    const float4 a = reinterpret_cast<const float4 *>(p)[0];
+    const float4 b = reinterpret_cast<const float4 *>(p)[1];
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) out[j] = j < nvalid ? p[j] : 0.0f;
+  }
+}
+
+template <bool FULL>
+__device__ __forceinline__ void load_bf16x8(const uint16_t *p, int nvalid, float (&out)[8]) {
+  if (FULL) {
+    const uint4 q = *reinterpret_cast<const uint4 *>(p);
+    out[0] = bf16_lo(q.x); out[1] = bf16_hi(q.x); out[2] = bf16_lo(q.y); out[3] = bf16_hi(q.y);
+    out[4] = bf16_lo(q.z); out[5] = bf16_hi(q.z); out[6] = bf16_lo(q.w); out[7] = bf16_hi(q.w);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) out[j] = j < nvalid ? u2f((uint32_t)p[j] << 16) : 0.0f;
+  }
+}
+
+template <bool FULL>
+__device__ __forceinline__ void store_f32x8(float *p, int nvalid, const float (&x)[8]) {
+  if (FULL) {
+    reinterpret_cast<float4 *>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
+    reinterpret_cast<float4 *>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < nvalid) p[j] = x[j];
+  }
+}
+
+template <bool FULL>
+__device__ __forceinline__ void store_bf16x8(uint16_t *p, int nvalid, const float (&x)[8]) {
+  uint32_t h[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) h[j] = f32_to_bf16_rne(x[j]);
+  if (FULL) {
+    *reinterpret_cast<uint4 *>(p) =
+        make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < nvalid) p[j] = (uint16_t)h[j];
+  }
+}
+
+template <bool BF16, bool FULL>
+__device__ __forceinline__ void load_state8(const void *base, uint64_t e0, int nvalid, float (&out)[8]) {
+  if (BF16) load_bf16x8<FULL>(static_cast<const uint16_t *>(base) + e0, nvalid, out);
+  else load_f32x8<FULL>(static_cast<const float *>(base) + e0, nvalid, out);
+}
+
+template <bool BF16, bool FULL>
+__device__ __forceinline__ void store_state8(void *base, uint64_t e0, int nvalid, const float (&x)[8]) {
+  if (BF16) store_bf16x8<FULL>(static_cast<uint16_t *>(base) + e0, nvalid, x);
+  else store_f32x8<FULL>(static_cast<float *>(base) + e0, nvalid, x);
+}
+
+// 8 codes of one lane: two dwords of E4M3 bytes, or one dword of INT4 nibbles (in c[0]).
+template <int FMT, bool FULL>
+__device__ __forceinline__ void load_codes8(const void *base, uint64_t e0, int nvalid, uint32_t (&c)[2]) {
+  const uint8_t *p = static_cast<const uint8_t *>(base) + (FMT == FMT_FP8 ? e0 : (e0 >> 1));
+  if (FULL) {
+    if (FMT == FMT_FP8) {
+      const uint2 q = *reinterpret_cast<const uint2 *>(p);
+      c[0] = q.x; c[1] = q.y;
+    } else {
+      c[0] = *reinterpret_cast<const uint32_t *>(p); c[1] = 0;
+    }
+  } else {
+    c[0] = 0; c[1] = 0;
+    const int nbytes = FMT == FMT_FP8 ? nvalid : (nvalid + 1) >> 1;
+    constexpr int MAXB = FMT == FMT_FP8 ? 8 : 4;
+#pragma unroll
+    for (int k = 0; k < MAXB; ++k)
+      if (k < nbytes) c[k >> 2] |= (uint32_t)p[k] << (8 * (k & 3));
+  }
+}
+
+template <int FMT, bool FULL>
+__device__ __forceinline__ void store_codes8(void *base, uint64_t e0, int nvalid, const uint32_t (&c)[2]) {
+  uint8_t *p = static_cast<uint8_t *>(base) + (FMT == FMT_FP8 ? e0 : (e0 >> 1));
+  if (FULL) {
+    if (FMT == FMT_FP8) *reinterpret_cast<uint2 *>(p) = make_uint2(c[0], c[1]);
+    else *reinterpret_cast<uint32_t *>(p) = c[0];
+  } else {
+    const int nbytes = FMT == FMT_FP8 ? nvalid : (nvalid + 1) >> 1;
+    constexpr int MAXB = FMT == FMT_FP8 ? 8 : 4;
+#pragma unroll
+    for (int k = 0; k < MAXB; ++k)
+      if (k < nbytes) p[k] = (uint8_t)(c[k >> 2] >> (8 * (k & 3)));
+  }
+}
+
+template <int FMT, int J>
+__device__ __forceinline__ float decode_elem(const uint32_t (&c)[2]) {
+  if (FMT == FMT_FP8) return e4m3_decode<(J & 3)>(c[J >> 2]);
+  return int4_decode(c[0], J);
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_scale(const void *scales, uint64_t blk) {
+  if (BF16) return u2f((uint32_t)static_cast<const uint16_t *>(scales)[blk] << 16);
+  return static_cast<const float *>(scales)[blk];
+}
+
+// abs-max scale of a block from the bit pattern of max|x| (wave-uniform within the block's lanes)
+template <int FMT, bool SCALE_BF16>
+__device__ __forceinline__ void block_scale(uint32_t amax_bits, float &s_new, float &inv) {
+  constexpr float RHO = FmtTraits<FMT>::RHO;
+  const float a = u2f(amax_bits);
+  s_new = a / RHO;
+  if (SCALE_BF16) {
+    s_new = u2f(f32_to_bf16_rne(s_new) << 16);
+    inv = 1.0f / s_new;
+  } else {
+    inv = RHO / a;
+  }
+  if (!(inv < __builtin_inff())) { s_new = 0.0f; inv = 0.0f; }   // a == 0, or rho/a overflows
+}
+
+// Encode 8 values y = x*inv onto the grid; returns packed codes.  r[4] = the lane's Philox words.
+template <int FMT, int ROUND, bool NORMAL_ONLY>
+__device__ __forceinline__ void encode8(const float (&y)[8], const Philox4 &r, uint32_t (&c)[2]) {
+  const uint32_t rw[4] = {r.w0, r.w1, r.w2, r.w3};
+  c[0] = 0; c[1] = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
+    if (FMT == FMT_FP8) c[j >> 2] |= e4m3_encode<ROUND, NORMAL_ONLY>(y[j], r16) << (8 * (j & 3));
+    else c[0] |= int4_encode<ROUND>(y[j], r16) << (4 * j);
+  }
+}
+
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int OPT, int ROUND, bool FULL>
+__device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &td, uint64_t e0) {
+  int nvalid = 8;
+  if (!FULL) {
+    const int64_t left = (int64_t)td.numel - (int64_t)e0;
+    nvalid = left >= 8 ? 8 : (left <= 0 ? 0 : (int)left);
+  }
+  const uint64_t blk = e0 >> a.bs_shift;
+
+  uint32_t c[2];
+  float g[8], m[8], v[8];
+  load_codes8<FMT, FULL>(td.w, e0, nvalid, c);
+  load_bf16x8<FULL>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
+  load_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
+  if (OPT == OPT_ADAM) load_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
+  const float s_old = (FULL || nvalid > 0) ? load_scale<SCALE_BF16>(td.s, blk) : 0.0f;
+
+  float w[8];
+  w[0] = decode_elem<FMT, 0>(c); w[1] = decode_elem<FMT, 1>(c); w[2] = decode_elem<FMT, 2>(c);
+  w[3] = decode_elem<FMT, 3>(c); w[4] = decode_elem<FMT, 4>(c); w[5] = decode_elem<FMT, 5>(c);
+  w[6] = decode_elem<FMT, 6>(c); w[7] = decode_elem<FMT, 7>(c);
+
+  // OPTIM_STEP on the de-quantized weights
+  float th[8], d[8];
+  uint32_t amax = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    float wj = w[j] * s_old;
+    m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
+    float u;
+    if (OPT == OPT_ADAM) {
+      v[j] = fmaf(a.b2, v[j], a.omb2 * (g[j] * g[j]));
+      d[j] = sqrtf(v[j] * a.rbc2) + a.eps;
+      u = (a.c1 * m[j]) / d[j];
+    } else {
+      d[j] = 0.0f;
+      u = a.lr * m[j];
+    }
+    if (a.wd != 0.0f) wj = wj - a.wd * wj;
+    th[j] = wj - u;
+    if (!FULL && j >= nvalid) th[j] = 0.0f;
+    const uint32_t ab = f2u(th[j]) & 0x7FFFFFFFu;
+    amax = amax > ab ? amax : ab;
+  }
+  if (OPT == OPT_ADAM) store_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);   // v is final (Alg. 3 returns it unchanged)
+
+  // ECO_QUANTIZE
+  amax = group_umax(amax, 1 << (a.bs_shift - 3));
+  float s_new, inv;
+  block_scale<FMT, SCALE_BF16>(amax, s_new, inv);
+
+  float y[8];
+  uint32_t ymin = 0xFFFFFFFFu;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    y[j] = th[j] * inv;
+    const uint32_t yb = f2u(y[j]) & 0x7FFFFFFFu;
+    ymin = ymin < yb ? ymin : yb;
+  }
+  Philox4 r = {0, 0, 0, 0};
+  if (ROUND == ROUND_SR) {
+    const uint64_t q = e0 >> 3;
+    r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
+  }
+  uint32_t cn[2];
+  if (FMT == FMT_FP8) {
+    // the E4M3 subnormal range (|y| < 2^-6) needs a second formula; it is rare, so decide per wave
+    if (__any(ymin < E4M3_MIN_NORMAL_BITS)) encode8<FMT, ROUND, false>(y, r, cn);
+    else encode8<FMT, ROUND, true>(y, r, cn);
+  } else {
+    encode8<FMT, ROUND, true>(y, r, cn);
+  }
+  store_codes8<FMT, FULL>(td.w, e0, nvalid, cn);
+
+  float qn[8];
+  qn[0] = decode_elem<FMT, 0>(cn); qn[1] = decode_elem<FMT, 1>(cn); qn[2] = decode_elem<FMT, 2>(cn);
+  qn[3] = decode_elem<FMT, 3>(cn); qn[4] = decode_elem<FMT, 4>(cn); qn[5] = decode_elem<FMT, 5>(cn);
+  qn[6] = decode_elem<FMT, 6>(cn); qn[7] = decode_elem<FMT, 7>(cn);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float e = th[j] - qn[j] * s_new;
+    if (OPT == OPT_ADAM) m[j] = fmaf(a.kappa * d[j], e, m[j]);
+    else m[j] = fmaf(a.alpha, e, m[j]);
+  }
+  store_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
+
+  // one lane per block stores the new scale
+  const uint32_t lanes_mask = (1u << (a.bs_shift - 3)) - 1u;
+  if ((threadIdx.x & lanes_mask) == 0 && (FULL || nvalid > 0)) {
+    if (SCALE_BF16) static_cast<uint16_t *>(td.s)[blk] = (uint16_t)(f2u(s_new) >> 16);
+    else static_cast<float *>(td.s)[blk] = s_new;
+  }
+}
+
+// The launch tables are read-only for the lifetime of a launch; reading them through the constant
+// address space lets the compiler fetch them with scalar loads (one per wave, into SGPRs) even
+// though the kernel also writes global memory.
+#define ECO_CONST_AS __attribute__((address_space(4)))
+
+__device__ __forceinline__ uint32_t load_tile_tensor(const StepArgs &a, uint32_t tile) {
+  const ECO_CONST_AS uint32_t *p = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.tile_tensor;
+  return p[tile];
+}
+
+__device__ __forceinline__ TensorDesc load_tensor_desc(const StepArgs &a, uint32_t ti) {
+  const ECO_CONST_AS uint64_t *p = (const ECO_CONST_AS uint64_t *)(uintptr_t)(a.tensors + ti);
+  TensorDesc td;
+  td.w = (void *)(uintptr_t)p[0];
+  td.s = (void *)(uintptr_t)p[1];
+  td.g = (const void *)(uintptr_t)p[2];
+  td.m = (void *)(uintptr_t)p[3];
+  td.v = (void *)(uintptr_t)p[4];
+  td.numel = p[5];
+  const uint64_t ft = p[6];
+  td.first_tile = (uint32_t)ft;
+  td.tensor_id = (uint32_t)(ft >> 32);
+  td.pad = 0;
+  return td;
+}
+
+// Persistent kernel: workgroup b handles tiles b, b + gridDim.x, ...  The tile -> tensor table and
+// the tensor descriptors are wave-uniform and are fetched with scalar loads.
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int OPT, int ROUND>
+__global__ __launch_bounds__(WG_THREADS) void eco_step_kernel(const StepArgs a) {
+  for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
+    const TensorDesc td = load_tensor_desc(a, load_tile_tensor(a, tile));
+    const uint64_t tile_off = (uint64_t)(tile - td.first_tile) * TILE_ELEMS;
+    const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+    if (tile_off + TILE_ELEMS <= td.numel) step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, true>(a, td, e0);
+    else step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, false>(a, td, e0);
+  }
+}
+
+template <int FMT, bool STATE_BF16>
+hipError_t launch_step_variants(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
+#define ECO_LAUNCH(SC, OP, RD)                                                                          \
+  hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(grid), dim3(WG_THREADS), 0,   \
+                     stream, args)
+  const int key = (kv.scale_bf16 ? 4 : 0) | (kv.opt == OPT_SGDM ? 2 : 0) | (kv.round == ROUND_RTN ? 1 : 0);
+  switch (key) {
+    case 0: ECO_LAUNCH(false, OPT_ADAM, ROUND_SR); break;
+    case 1: ECO_LAUNCH(false, OPT_ADAM, ROUND_RTN); break;
+    case 2: ECO_LAUNCH(false, OPT_SGDM, ROUND_SR); break;
+    case 3: ECO_LAUNCH(false, OPT_SGDM, ROUND_RTN); break;
+    case 4: ECO_LAUNCH(true, OPT_ADAM, ROUND_SR); break;
+    case 5: ECO_LAUNCH(true, OPT_ADAM, ROUND_RTN); break;
+    case 6: ECO_LAUNCH(true, OPT_SGDM, ROUND_SR); break;
+    default: ECO_LAUNCH(true, OPT_SGDM, ROUND_RTN); break;
+  }
+#undef ECO_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace eco

@@ -1,0 +1,137 @@
+"""Device-side set-up of a synthetic workload for the ECO library: memory, initial quantization, plan.
+
+PyTorch is used for device memory, streams and random gradients only; every operation of the
+method (initial quantization included) is a call into libeco.so through the binding.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional
+
+import torch
+
+import workloads
+from workloads import Workload
+
+from . import binding as eco
+
+_FMT = {"fp8": eco.ECO_FMT_FP8_E4M3, "int4": eco.ECO_FMT_INT4, "bf16_plain": eco.ECO_FMT_BF16_PLAIN,
+        "fp32_identity": eco.ECO_FMT_FP32_IDENTITY}
+
+
+def _round_up(x: int, k: int) -> int:
+    return (x + k - 1) // k * k
+
+
+@dataclass
+class TensorViews:
+    spec: workloads.TensorSpec
+    tensor_id: int
+    fmt: int
+    weights: torch.Tensor          # uint8 codes, or bf16 / fp32 weights
+    scales: Optional[torch.Tensor]
+    grad: torch.Tensor             # bf16
+    m: torch.Tensor
+    v: torch.Tensor
+
+
+class DeviceWorkload:
+    """All tensors of a workload resident in HBM, carved out of a few flat arenas (one per array
+    kind) so that a multi-thousand-tensor model costs a handful of allocations; each tensor still
+    has its own descriptor in the plan and its own, 256-byte aligned, slices."""
+
+    def __init__(self, wl: Workload, device: str = "cuda:0", base_seed: int = workloads.BASE_SEED,
+                 init: bool = True):
+        self.wl = wl
+        self.device = torch.device(device)
+        self.base_seed = base_seed
+        self.state_dtype = torch.bfloat16 if wl.state_bf16 else torch.float32
+        self.scale_dtype = torch.bfloat16 if wl.scale_bf16 else torch.float32
+        bs = wl.block_size
+
+        # element offsets: multiples of 512 keep every slice (down to 4-bit codes) 256-byte aligned
+        off = 0
+        offs, soffs = [], []
+        soff = 0
+        code_bytes = 0
+        coffs = []
+        woffs, woff = [], 0
+        for t in wl.tensors:
+            offs.append(off)
+            off += _round_up(t.numel, 512)
+            if t.fmt in ("fp8", "int4"):
+                soffs.append(soff)
+                soff += _round_up((t.numel + bs - 1) // bs, 128)
+                coffs.append(code_bytes)
+                nbytes = t.numel if t.fmt == "fp8" else (t.numel + 1) // 2
+                code_bytes += _round_up(nbytes, 256)
+                woffs.append(-1)
+            else:
+                soffs.append(-1)
+                coffs.append(-1)
+                woffs.append(woff)
+                woff += _round_up(t.numel, 512)
+        dev = self.device
+        self.codes = torch.zeros(max(code_bytes, 1), dtype=torch.uint8, device=dev)
+        self.scales = torch.zeros(max(soff, 1), dtype=self.scale_dtype, device=dev)
+        self.plain = torch.zeros(max(woff, 1), dtype=torch.bfloat16, device=dev)
+        self.grad = torch.zeros(off, dtype=torch.bfloat16, device=dev)
+        self.m = torch.zeros(off, dtype=self.state_dtype, device=dev)
+        self.v = torch.zeros(off, dtype=self.state_dtype, device=dev)
+
+        self.tensors: List[TensorViews] = []
+        for i, t in enumerate(wl.tensors):
+            n = t.numel
+            if t.fmt in ("fp8", "int4"):
+                nbytes = n if t.fmt == "fp8" else (n + 1) // 2
+                w = self.codes[coffs[i]:coffs[i] + nbytes]
+                s = self.scales[soffs[i]:soffs[i] + (n + bs - 1) // bs]
+            else:
+                w = self.plain[woffs[i]:woffs[i] + n]
+                s = None
+            o = offs[i]
+            self.tensors.append(TensorViews(t, i, _FMT[t.fmt], w, s, self.grad[o:o + n], self.m[o:o + n],
+                                            self.v[o:o + n]))
+        if init:
+            self.init_weights()
+        self.plan = eco.Plan([self.descriptor(tv) for tv in self.tensors], self.hparams(1))
+
+    # ------------------------------------------------------------------ set-up
+    @property
+    def numel(self) -> int:
+        return self.wl.numel
+
+    def descriptor(self, tv: TensorViews) -> "eco.eco_tensor_t":
+        return eco.make_tensor(tv.weights, tv.scales, tv.grad, tv.m, tv.v, tv.spec.numel, tv.tensor_id, tv.fmt)
+
+    def hparams(self, step: int, **over) -> "eco.eco_hparams_t":
+        wl = self.wl
+        kw = dict(block_size=wl.block_size,
+                  state_dtype=eco.ECO_DT_BF16 if wl.state_bf16 else eco.ECO_DT_FP32,
+                  scale_dtype=eco.ECO_DT_BF16 if wl.scale_bf16 else eco.ECO_DT_FP32,
+                  lr=wl.lr_at(step), beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, step=step, seed=self.base_seed)
+        kw.update(over)
+        return eco.make_hparams(**kw)
+
+    def init_weights(self) -> None:
+        """fp32 N(0, sigma) weights -> round-to-nearest quantization by the library."""
+        wl = self.wl
+        for tv in self.tensors:
+            w = workloads.initial_weights(wl, tv.tensor_id, device=self.device, base_seed=self.base_seed)
+            if tv.fmt in (eco.ECO_FMT_FP8_E4M3, eco.ECO_FMT_INT4):
+                eco.eco_quantize_init(w, eco.ECO_DT_FP32, tv.spec.numel, tv.fmt, wl.block_size,
+                                      eco.ECO_DT_BF16 if wl.scale_bf16 else eco.ECO_DT_FP32, tv.weights, tv.scales)
+            else:
+                tv.weights.copy_(w.to(torch.bfloat16))
+            del w
+        torch.cuda.synchronize(self.device)
+
+    def fill_gradients(self, step: int) -> None:
+        for tv in self.tensors:
+            workloads.gradient(self.wl, tv.tensor_id, step, device=self.device, base_seed=self.base_seed, out=tv.grad)
+
+    def step(self, step: int, **over) -> None:
+        self.plan.step(self.hparams(step, **over))
+
+    def close(self) -> None:
+        self.plan.close()

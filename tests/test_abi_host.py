@@ -1,0 +1,146 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol that
+include/eco.h declares, validates its arguments before touching the device, and derives the
+step constants as documented."""
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def eco():
+    lib_path = os.path.join(ROOT, "paper_2601_22101_amd", "libeco.so")
+    if not os.path.exists(lib_path):
+        from paper_2601_22101_amd import build
+        build.build()
+    from paper_2601_22101_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(eco):
+    header = open(os.path.join(ROOT, "include", "eco.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(eco_[a-z_0-9]+)\s*\(", header))
+    assert {"eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_quantize_init",
+            "eco_dequantize", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_status_string",
+            "eco_last_error", "eco_version"} <= names
+    for n in names:
+        assert hasattr(eco.lib, n), n
+    assert eco.eco_version() >= 100
+    assert eco.eco_status_string(0) == "ok" and "align" in eco.eco_status_string(eco.ECO_EALIGN)
+
+
+def test_struct_layouts_match_header(eco):
+    assert C.sizeof(eco.eco_tensor_t) == 56
+    assert C.sizeof(eco.eco_hparams_t) == 80
+    assert C.sizeof(eco.eco_constants_t) == 48
+
+
+def _tensor(eco, **kw):
+    base = dict(weights=0x1000, scales=0x2000, grad=0x3000, m=0x4000, v=0x5000, numel=4096, tensor_id=0,
+                fmt=eco.ECO_FMT_FP8_E4M3)
+    base.update(kw)
+    return eco.make_tensor(**base)
+
+
+def _status(eco, fn, *args):
+    try:
+        fn(*args)
+    except eco.EcoError as e:
+        return e.status
+    return 0
+
+
+def test_plan_validation_happens_before_any_device_work(eco):
+    hp = eco.make_hparams()
+    bad = [
+        (dict(numel=0), eco.ECO_EINVAL),
+        (dict(weights=None), eco.ECO_EINVAL),
+        (dict(grad=None), eco.ECO_EINVAL),
+        (dict(m=None), eco.ECO_EINVAL),
+        (dict(v=None), eco.ECO_EINVAL),              # Adam needs v
+        (dict(scales=None), eco.ECO_EINVAL),         # quantized format needs scales
+        (dict(fmt=7), eco.ECO_EINVAL),
+        (dict(weights=0x1008), eco.ECO_EALIGN),
+        (dict(m=0x4004), eco.ECO_EALIGN),
+        (dict(grad=0x3002), eco.ECO_EALIGN),
+    ]
+    for kw, want in bad:
+        assert _status(eco, eco.eco_plan_create, [_tensor(eco, **kw)], hp) == want, kw
+        assert eco.eco_last_error()
+    assert _status(eco, eco.eco_plan_create, [], hp) == eco.ECO_EINVAL
+    for bs, want in ((0, eco.ECO_EINVAL), (16, eco.ECO_EUNSUPPORTED), (100, eco.ECO_EUNSUPPORTED),
+                     (1024, eco.ECO_EUNSUPPORTED)):
+        assert _status(eco, eco.eco_plan_create, [_tensor(eco)], eco.make_hparams(block_size=bs)) == want
+    assert _status(eco, eco.eco_plan_create, [_tensor(eco)], eco.make_hparams(state_dtype=5)) == eco.ECO_EINVAL
+    # SGDM does not need v
+    st = _status(eco, eco.eco_plan_create, [_tensor(eco, v=None)], eco.make_hparams(opt=eco.ECO_OPT_SGDM))
+    assert st in (eco.ECO_OK, eco.ECO_EHIP, eco.ECO_ENOMEM)      # passes validation; no GPU here -> HIP error
+
+
+def test_hparams_validation(eco):
+    ok = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=1)
+    eco.eco_step_constants(eco.make_hparams(**ok))
+    for kw in (dict(step=0), dict(lr=0.0), dict(lr=-1.0), dict(lr=float("nan")), dict(beta1=0.0), dict(beta1=1.0),
+               dict(beta2=1.0), dict(beta2=-0.1), dict(eps=-1.0), dict(weight_decay=-0.1), dict(opt=3),
+               dict(round=2), dict(inject=2), dict(state_dtype=9)):
+        assert _status(eco, eco.eco_step_constants, eco.make_hparams(**{**ok, **kw})) == eco.ECO_EINVAL, kw
+    # without injection nothing divides by lr or beta1
+    eco.eco_step_constants(eco.make_hparams(**{**ok, "lr": 0.0, "inject": False}))
+    eco.eco_step_constants(eco.make_hparams(**{**ok, "beta1": 0.0, "inject": False}))
+    # the validation precedes the plan in the plan-less entry point as well
+    assert _status(eco, eco.eco_step_tensors, [_tensor(eco)], eco.make_hparams(step=0), 0) == eco.ECO_EINVAL
+
+
+def test_flat_helpers_validate(eco):
+    q = lambda **kw: _status(eco, eco.eco_quantize_init, kw.get("src", 0x1000), kw.get("sdt", 0), kw.get("n", 1024),
+                             kw.get("fmt", 0), kw.get("bs", 128), kw.get("scdt", 0), kw.get("w", 0x2000),
+                             kw.get("s", 0x3000), 0)
+    assert q(n=0) == eco.ECO_EINVAL
+    assert q(src=None) == eco.ECO_EINVAL
+    assert q(w=None) == eco.ECO_EINVAL
+    assert q(fmt=2) == eco.ECO_EINVAL
+    assert q(bs=48) == eco.ECO_EUNSUPPORTED
+    assert q(src=0x1004) == eco.ECO_EALIGN
+    assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 1024, 0, 128, 0, None, 0) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 0, 0x1000, 0) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 16, None, 0) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_set_option, 5, 1) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_set_option, 0, 1000) == eco.ECO_EINVAL
+    eco.eco_set_option(0, 0)
+
+
+def test_step_constants_follow_the_paper(eco):
+    """kappa = ((1-b1^k)/lr)(1-1/b1) (Alg. 3 line 5), alpha = (1/lr)(1-1/b) (Eq. alpha), the Adam step
+    lr/(1-b1^k) and 1/(1-b2^k) (Sec. 3.2): formed in double, rounded once to fp32."""
+    for lr, b1, b2, eps, wd, k in ((1e-3, 0.9, 0.999, 1e-8, 0.0, 1), (3e-4, 0.9, 0.98, 1e-9, 0.1, 17),
+                                   (1e-5, 0.95, 0.999, 1e-8, 0.01, 100000)):
+        c = eco.eco_step_constants(eco.make_hparams(lr=lr, beta1=b1, beta2=b2, eps=eps, weight_decay=wd, step=k))
+        f = np.float32
+        bc1, bc2 = 1 - b1 ** k, 1 - b2 ** k
+        assert c.b1 == f(b1) and c.omb1 == f(1 - b1) and c.b2 == f(b2) and c.omb2 == f(1 - b2)
+        assert c.eps == f(eps) and c.lr == f(lr) and c.wd == f(lr * wd)
+        for got, want in ((c.rbc2, 1 / bc2), (c.c1, lr / bc1), (c.kappa, (bc1 / lr) * (1 - 1 / b1)),
+                          (c.alpha, (1 / lr) * (1 - 1 / b1))):
+            assert abs(got - want) <= abs(want) * 2.0 ** -23
+        assert c.kappa < 0 and c.alpha < 0
+    c = eco.eco_step_constants(eco.make_hparams(inject=False))
+    assert c.kappa == 0 and c.alpha == 0
+
+
+def test_product_package_never_reaches_the_oracle():
+    """The product path must not import, read or link anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2601_22101_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for fn in files:
+            if fn.endswith((".py", ".cpp", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), fn
+                assert "eco_oracle" not in text and "liboracle" not in text, fn

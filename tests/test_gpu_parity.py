@@ -1,0 +1,314 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, element by element
+on the same seeded inputs.  Sizes span several 2048-element tiles and ragged tails; the bar is in
+tests/gpu_util.py."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from oracle import FMT_E4M3, FMT_INT4
+
+from gpu_util import bf16_bits, compare, host_copy, oracle_step, step_config, to_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def eco():
+    from paper_2601_22101_amd import binding
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return binding
+
+
+@pytest.fixture(scope="module")
+def harness():
+    from paper_2601_22101_amd import harness
+    return harness
+
+
+DEV = "cuda:0"
+
+
+# ---------------------------------------------------------------------------------- building blocks
+
+def test_philox_stream_is_bit_exact(eco, o32):
+    for seed, step, tid, first, n in ((0, 1, 0, 0, 4096), (0x0123456789ABCDEF, 7, 42, 0, 1000),
+                                      (99, 3, 5, 13, 3001), (5, 2 ** 32 + 9, 1, (1 << 34) - 6, 64)):
+        dst = torch.zeros(n, dtype=torch.int32, device=DEV)
+        eco.eco_philox_fill(seed, step, tid, first, n, dst)
+        got = dst.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, o32.philox_fill(seed, step, tid, n, first_word=first)), (seed, step, tid, first)
+
+
+def test_decode_every_code(eco, o32):
+    codes = torch.arange(256, dtype=torch.uint8, device=DEV)
+    scales = torch.ones(2, dtype=torch.float32, device=DEV)
+    out = torch.zeros(256, dtype=torch.float32, device=DEV)
+    eco.eco_dequantize(codes, scales, 256, eco.ECO_FMT_FP8_E4M3, 128, eco.ECO_DT_FP32, out)
+    got, ref = out.cpu().numpy(), o32.decode_table(FMT_E4M3)
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got[ok].view(np.uint32), ref[ok].view(np.uint32))
+    nib = torch.tensor([0x10, 0x32, 0x54, 0x76, 0x98, 0xBA, 0xDC, 0xFE] * 4, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(64, dtype=torch.float32, device=DEV)
+    eco.eco_dequantize(nib, scales, 64, eco.ECO_FMT_INT4, 32, eco.ECO_DT_FP32, out)
+    assert np.array_equal(out.cpu().numpy()[:16], o32.decode_table(FMT_INT4))
+
+
+@pytest.mark.parametrize("fmt", [0, 1])
+@pytest.mark.parametrize("scale_bf16", [False, True])
+@pytest.mark.parametrize("numel,bs", [(1024 * 1024, 128), (2048 * 3 + 1000, 128), (4099, 32), (5000, 64),
+                                      (777, 256), (9000, 512), (7, 128)])
+def test_quantize_init_matches_oracle(eco, o32, fmt, scale_bf16, numel, bs):
+    g = torch.Generator().manual_seed(numel + bs)
+    x = torch.randn(numel, generator=g) * 0.02
+    x[::97] = 0.0
+    if numel > 3000:
+        x[2048:2048 + bs] = 0.0                       # an all-zero block
+        x[1024:1024 + bs] *= 1e-30                    # a block whose scale underflows towards zero
+    sdt = torch.bfloat16 if scale_bf16 else torch.float32
+    nb = (numel + bs - 1) // bs
+    xd = x.to(DEV)
+    codes = torch.zeros(numel if fmt == 0 else (numel + 1) // 2, dtype=torch.uint8, device=DEV)
+    scales = torch.zeros(nb, dtype=sdt, device=DEV)
+    eco.eco_quantize_init(xd, eco.ECO_DT_FP32, numel, fmt, bs, int(scale_bf16), codes, scales)
+    rc, rs = o32.quantize_rtn(fmt, x.numpy(), block_size=bs, scale_bf16=scale_bf16)
+    assert np.array_equal(codes.cpu().numpy(), rc)
+    assert np.array_equal(to_f32(scales).view(np.uint32), rs.view(np.uint32))
+    # and back
+    out = torch.zeros(numel, dtype=torch.float32, device=DEV)
+    eco.eco_dequantize(codes, scales, numel, fmt, bs, int(scale_bf16), out)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), o32.dequantize(fmt, rc, rs, numel, bs).view(np.uint32))
+    # bf16 source
+    xb = x.to(torch.bfloat16)
+    eco.eco_quantize_init(xb.to(DEV), eco.ECO_DT_BF16, numel, fmt, bs, int(scale_bf16), codes, scales)
+    rc, rs = o32.quantize_rtn(fmt, xb.float().numpy(), block_size=bs, scale_bf16=scale_bf16)
+    assert np.array_equal(codes.cpu().numpy(), rc)
+
+
+# ---------------------------------------------------------------------------------- whole workloads
+
+def run_workload_parity(harness, o32, wl, steps, base_seed=workloads.BASE_SEED, **over):
+    """Every tensor, every step: the library on the device, the oracle on host copies of the same bits."""
+    dw = harness.DeviceWorkload(wl, DEV, base_seed)
+    host = [host_copy(tv) for tv in dw.tensors]
+    # the initial round-to-nearest quantization is itself part of the path: check it against the oracle's
+    for tv, h in zip(dw.tensors, host):
+        if tv.scales is not None:
+            w0 = workloads.initial_weights(wl, tv.tensor_id, device=DEV, base_seed=base_seed).cpu().numpy()
+            rc, rs = o32.quantize_rtn(oracle.FMT_E4M3 if tv.fmt == 0 else oracle.FMT_INT4, w0, wl.block_size,
+                                      wl.scale_bf16)
+            assert np.array_equal(h["codes"], rc) and np.array_equal(h["scales"].view(np.uint32), rs.view(np.uint32))
+    worst = {}
+    for k in range(1, steps + 1):
+        dw.fill_gradients(k)
+        hp = dw.hparams(k, **over)
+        for tv, h in zip(dw.tensors, host):
+            h["grad"] = bf16_bits(tv.grad)
+        dw.plan.step(hp)
+        torch.cuda.synchronize()
+        for tv, h in zip(dw.tensors, host):
+            oracle_step(o32, h, tv.spec.numel, step_config(hp, tv.tensor_id, tv.fmt))
+            st = compare(host_copy(tv), h, f"{wl.name} step {k} tensor {tv.spec.name}", wl.state_bf16)
+            for key, val in st.items():
+                worst[key] = max(worst.get(key, 0), val)
+    dw.close()
+    return worst
+
+
+def test_config1_every_step(harness, o32):
+    worst = run_workload_parity(harness, o32, workloads.config1(), steps=10)
+    assert worst["code_mismatch"] == 0 and worst["m_bit_mismatch"] == 0 and worst["v_bit_mismatch"] == 0, worst
+
+
+def test_config2_multi_tensor_every_step(harness, o32):
+    wl = workloads.config2()
+    worst = run_workload_parity(harness, o32, wl, steps=wl.steps)
+    assert worst["code_mismatch"] == 0, worst
+
+
+def small_mixed_workload(fmt="fp8", **kw):
+    """A few tensors of awkward sizes: below one tile, ragged tiles, ragged blocks, odd lengths."""
+    T = workloads.TensorSpec
+    sizes = [(64, 1024), (3, 2048), (2048 * 2 + 128 * 5,), (128 * 9 + 40,), (7,), (4097,), (1,), (2048,), (513, 9)]
+    ts = [T(f"t{i}", s, fmt, grad_std=1e-3 * (1 + i)) for i, s in enumerate(sizes)]
+    ts.insert(3, T("norm", (512,), "bf16_plain"))
+    ts.insert(6, T("norm_ragged", (1000,), "bf16_plain"))
+    return workloads.Workload("mixed_" + fmt, ts, steps=4, **kw)
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
+@pytest.mark.parametrize("opt,rnd,inject,wd", [(0, 0, True, 0.0), (0, 1, True, 0.0), (1, 0, True, 0.0),
+                                               (1, 1, True, 0.1), (0, 0, False, 0.0), (0, 0, True, 0.1)])
+def test_variants_on_ragged_tensors(harness, o32, fmt, opt, rnd, inject, wd):
+    wl = small_mixed_workload(fmt)
+    over = dict(opt=opt, round=rnd, inject=inject, weight_decay=wd)
+    if opt == 1:
+        over["lr"] = 0.05
+    # the plan is built from hparams(1) of the workload, which is Adam: rebuild for SGDM
+    dw_over = dict(over)
+    worst = _run_with_layout(harness, o32, wl, 4, dw_over)
+    assert worst["code_mismatch"] == 0, worst
+
+
+def _run_with_layout(harness, o32, wl, steps, over):
+    from paper_2601_22101_amd import binding as eco
+    dw = harness.DeviceWorkload(wl, DEV)
+    dw.plan.close()
+    dw.plan = eco.Plan([dw.descriptor(tv) for tv in dw.tensors], dw.hparams(1, **over))
+    host = [host_copy(tv) for tv in dw.tensors]
+    worst = {}
+    for k in range(1, steps + 1):
+        dw.fill_gradients(k)
+        hp = dw.hparams(k, **over)
+        for tv, h in zip(dw.tensors, host):
+            h["grad"] = bf16_bits(tv.grad)
+        dw.plan.step(hp)
+        torch.cuda.synchronize()
+        for tv, h in zip(dw.tensors, host):
+            oracle_step(o32, h, tv.spec.numel, step_config(hp, tv.tensor_id, tv.fmt))
+            st = compare(host_copy(tv), h, f"{wl.name} step {k} {tv.spec.name} {over}", wl.state_bf16)
+            for key, val in st.items():
+                worst[key] = max(worst.get(key, 0), val)
+    dw.close()
+    return worst
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
+@pytest.mark.parametrize("bs", [32, 64, 256, 512])
+def test_block_sizes(harness, o32, fmt, bs):
+    wl = small_mixed_workload(fmt, block_size=bs)
+    worst = _run_with_layout(harness, o32, wl, 3, {})
+    assert worst["code_mismatch"] == 0, worst
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
+def test_bf16_state_and_scales(harness, o32, fmt):
+    wl = small_mixed_workload(fmt, state_bf16=True, scale_bf16=True, lr=1e-4)
+    worst = _run_with_layout(harness, o32, wl, 4, {})
+    assert worst["code_mismatch"] == 0, worst
+
+
+def test_identity_format_is_plain_adam(harness, eco, o32):
+    """ECO_FMT_FP32_IDENTITY on the device against torch's own Adam (the library comparator of the oracle's pin)."""
+    n = 5000
+    g = torch.Generator().manual_seed(3)
+    w0 = torch.randn(n, generator=g) * 0.02
+    w = w0.to(DEV).clone()
+    m = torch.zeros(n, device=DEV)
+    v = torch.zeros(n, device=DEV)
+    grad = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    p = torch.nn.Parameter(w0.double().clone())
+    opt = torch.optim.Adam([p], lr=1e-3, betas=(0.9, 0.999), eps=1e-8)
+    t = eco.make_tensor(w, None, grad, m, v, n, 0, eco.ECO_FMT_FP32_IDENTITY)
+    with eco.Plan([t], eco.make_hparams()) as plan:
+        for k in range(1, 11):
+            gk = (torch.randn(n, generator=g) * 1e-3).to(torch.bfloat16)
+            grad.copy_(gk)
+            p.grad = gk.double()
+            opt.step()
+            plan.step(eco.make_hparams(step=k))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(w.cpu().numpy(), p.detach().numpy(), rtol=2e-5, atol=1e-8)
+    np.testing.assert_allclose(m.cpu().numpy(), opt.state[p]["exp_avg"].numpy(), rtol=2e-5, atol=1e-12)
+    np.testing.assert_allclose(v.cpu().numpy(), opt.state[p]["exp_avg_sq"].numpy(), rtol=2e-5, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------- invariances and edge cases
+
+def _snapshot(dw):
+    return [(tv.weights.clone(), None if tv.scales is None else tv.scales.clone(), tv.m.clone(), tv.v.clone())
+            for tv in dw.tensors]
+
+
+def _equal(a, b):
+    return all(all((x is None and y is None) or torch.equal(x, y) for x, y in zip(ta, tb)) for ta, tb in zip(a, b))
+
+
+def test_results_do_not_depend_on_launch_geometry_or_plan_order(harness, eco):
+    wl = small_mixed_workload("fp8")
+    results = []
+    for wgs, reverse in ((0, False), (1, False), (3, True)):
+        eco.eco_set_option(0, wgs)
+        dw = harness.DeviceWorkload(wl, DEV)
+        if reverse:
+            dw.plan.close()
+            dw.plan = eco.Plan([dw.descriptor(tv) for tv in reversed(dw.tensors)], dw.hparams(1))
+        for k in (1, 2, 3):
+            dw.fill_gradients(k)
+            dw.step(k)
+        torch.cuda.synchronize()
+        results.append(_snapshot(dw))
+        dw.close()
+    eco.eco_set_option(0, 0)
+    assert _equal(results[0], results[1]) and _equal(results[0], results[2])
+
+
+def test_plan_less_entry_point_and_resume(harness, eco):
+    """eco_step_tensors gives the same bytes as a plan; and because the state is only (codes, scales,
+    m, v) plus (seed, step), stopping after 2 steps and continuing equals 4 steps in a row."""
+    wl = small_mixed_workload("fp8")
+    a = harness.DeviceWorkload(wl, DEV)
+    b = harness.DeviceWorkload(wl, DEV)
+    for k in (1, 2, 3, 4):
+        a.fill_gradients(k)
+        a.step(k)
+    for k in (1, 2):
+        b.fill_gradients(k)
+        eco.eco_step_tensors([b.descriptor(tv) for tv in b.tensors], b.hparams(k))
+    saved = _snapshot(b)
+    c = harness.DeviceWorkload(wl, DEV, init=False)
+    for tv, (w, s, m, v) in zip(c.tensors, saved):
+        tv.weights.copy_(w)
+        if s is not None:
+            tv.scales.copy_(s)
+        tv.m.copy_(m)
+        tv.v.copy_(v)
+    for k in (3, 4):
+        c.fill_gradients(k)
+        c.step(k)
+    torch.cuda.synchronize()
+    assert _equal(_snapshot(a), _snapshot(c))
+    for d in (a, b, c):
+        d.close()
+
+
+def test_zero_gradient_and_zero_blocks(harness, eco, o32):
+    """Inactive experts still take the full step (Adam with g = 0 is not a no-op); all-zero weights with
+    zero gradient stay zero with scale 0."""
+    n = 2048 * 2 + 300
+    g = torch.Generator().manual_seed(8)
+    w0 = torch.randn(n, generator=g) * 0.02
+    w0[:256] = 0.0
+    codes = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    scales = torch.zeros((n + 127) // 128, device=DEV)
+    eco.eco_quantize_init(w0.to(DEV), 0, n, 0, 128, 0, codes, scales)
+    m = (torch.randn(n, generator=g) * 1e-4).to(DEV)
+    m[:256] = 0.0
+    v = (torch.rand(n, generator=g) * 1e-8).to(DEV)
+    grad = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+
+    class TV:
+        pass
+    tv = TV()
+    tv.weights, tv.scales, tv.grad, tv.m, tv.v = codes, scales, grad, m, v
+    h = host_copy(tv)
+    hp = eco.make_hparams(step=5, seed=77)
+    eco.eco_step_tensors([eco.make_tensor(codes, scales, grad, m, v, n, 9, 0)], hp)
+    oracle_step(o32, h, n, step_config(hp, 9, 0))
+    st = compare(host_copy(tv), h, "zero gradient")
+    assert st["code_mismatch"] == 0
+    assert torch.all(codes[:256] == 0) and torch.all(scales[:2] == 0) and torch.all(m[:256] == 0)
+    assert not torch.equal(m[256:], torch.zeros_like(m[256:]))
+
+
+def test_step_rejects_a_layout_that_differs_from_the_plan(harness, eco):
+    wl = workloads.Workload("tiny", [workloads.TensorSpec("w", (4096,))], steps=1)
+    dw = harness.DeviceWorkload(wl, DEV)
+    for over in (dict(block_size=64), dict(state_dtype=1), dict(scale_dtype=1), dict(opt=1)):
+        with pytest.raises(eco.EcoError) as ei:
+            dw.plan.step(dw.hparams(1, **over))
+        assert ei.value.status == eco.ECO_EINVAL
+    with pytest.raises(eco.EcoError):
+        dw.plan.step(dw.hparams(0))
+    dw.close()

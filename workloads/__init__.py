@@ -161,7 +161,10 @@ def initial_weights(wl: Workload, tensor_id: int, device="cpu", base_seed: int =
     """fp32 N(0, weight_std) weights of one tensor, flattened."""
     t = wl.tensors[tensor_id]
     g = _gen(device, base_seed, 0x57, tensor_id)
-    return torch.randn(t.numel, generator=g, device=device, dtype=torch.float32) * wl.weight_std
+    w = torch.randn(t.numel, generator=g, device=device, dtype=torch.float32) * wl.weight_std
+    if t.fmt == "bf16_plain":            # norm gains start around one
+        w += 1.0
+    return w
 
 
 def inactive_experts(wl: Workload, step: int, layer: int, base_seed: int = BASE_SEED) -> set:
