@@ -95,9 +95,10 @@ void derive_constants(const eco_hparams_t *hp, eco_constants_t *c) {
 
 struct Group {
   std::vector<eco::TensorDesc> descs;
-  std::vector<uint32_t> tile_tensor;
+  std::vector<uint32_t> tile_tensor;     // one entry per full tile
+  std::vector<uint32_t> ragged_tensor;   // tensors whose last tile is partial
   eco::TensorDesc *d_descs = nullptr;
-  uint32_t *d_tiles = nullptr;
+  uint32_t *d_tiles = nullptr;           // tile_tensor followed by ragged_tensor
 };
 
 int num_compute_units() {
@@ -145,7 +146,7 @@ int eco_version(void) { return 100; }
 
 eco_status_t eco_set_option(int32_t option, int64_t value) {
   if (option != 0) return fail(ECO_EINVAL, "unknown option %d", option);
-  if (value < 0 || value > 64) return fail(ECO_EINVAL, "workgroups per compute unit must lie in [0, 64]");
+  if (value < 0 || value > 65536) return fail(ECO_EINVAL, "workgroups per compute unit must lie in [0, 65536]");
   g_wgs_per_cu = value;
   return ECO_OK;
 }
@@ -209,7 +210,7 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
         break;
       }
       Group &g = plan->groups[t.fmt];
-      const uint64_t ntiles = (t.numel + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS;
+      const uint64_t ntiles = t.numel / eco::TILE_ELEMS;   // full tiles
       if (g.tile_tensor.size() + ntiles > 0xFFFFFFF0ull) { st = fail(ECO_EUNSUPPORTED, "plan: more than 2^32 tiles in one format"); break; }
       eco::TensorDesc d;
       std::memset(&d, 0, sizeof d);
@@ -220,6 +221,7 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
       const uint32_t idx = static_cast<uint32_t>(g.descs.size());
       g.descs.push_back(d);
       g.tile_tensor.insert(g.tile_tensor.end(), static_cast<size_t>(ntiles), idx);
+      if (t.numel % eco::TILE_ELEMS) g.ragged_tensor.push_back(idx);
     }
   } catch (const std::bad_alloc &) {
     st = fail(ECO_ENOMEM, "plan: host allocation failed");
@@ -230,9 +232,11 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   for (Group &g : plan->groups) {
     if (g.descs.empty()) continue;
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&g.d_descs), g.descs.size() * sizeof(eco::TensorDesc));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&g.d_tiles), g.tile_tensor.size() * sizeof(uint32_t));
+    const size_t nt = g.tile_tensor.size(), nr = g.ragged_tensor.size();
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&g.d_tiles), (nt + nr) * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemcpy(g.d_descs, g.descs.data(), g.descs.size() * sizeof(eco::TensorDesc), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(g.d_tiles, g.tile_tensor.data(), g.tile_tensor.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess && nt) e = hipMemcpy(g.d_tiles, g.tile_tensor.data(), nt * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess && nr) e = hipMemcpy(g.d_tiles + nt, g.ragged_tensor.data(), nr * sizeof(uint32_t), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       st = (e == hipErrorOutOfMemory) ? fail(ECO_ENOMEM, "plan: device allocation failed") : fail_hip(e, "plan upload");
       (void)eco_plan_destroy(plan);
@@ -259,7 +263,9 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     eco::StepArgs a;
     a.tensors = g.d_descs;
     a.tile_tensor = g.d_tiles;
+    a.ragged_tensor = g.d_tiles + g.tile_tensor.size();
     a.num_tiles = static_cast<uint32_t>(g.tile_tensor.size());
+    a.num_ragged = static_cast<uint32_t>(g.ragged_tensor.size());
     a.bs_shift = static_cast<uint32_t>(plan->bs_shift);
     a.b1 = c.b1; a.omb1 = c.omb1; a.b2 = c.b2; a.omb2 = c.omb2; a.rbc2 = c.rbc2; a.c1 = c.c1; a.eps = c.eps;
     a.kappa = c.kappa; a.lr = c.lr; a.alpha = c.alpha; a.wd = c.wd;

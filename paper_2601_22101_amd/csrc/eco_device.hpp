@@ -27,20 +27,28 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 }
 
 // ---------------------------------------------------------------------------------- E4M3 (OCP)
-// Decode byte `sel` of a dword holding four codes.  Code c = S.EEEE.MMM; (c & 0x7F) << 20 placed
-// in an fp32 has exponent field E and the mantissa's top bits MMM, i.e. the value
-// 2^(E-127) * (1 + M/8) for E >= 1 and the fp32 subnormal M * 2^-129 for E = 0; multiplying by
-// 2^120 gives 2^(E-7)(1+M/8) resp. M * 2^-9, which is the E4M3 value.  The product is exact.
+// Decode byte SEL of a dword holding four codes.  gfx950's fp8 conversion instructions implement
+// the OCP E4M3 encoding (bias 7, subnormals, S.1111.111 = NaN), and a decode is exact, so the
+// hardware instruction is used; the GPU tests decode all 256 codes against the format definition.
 template <int SEL>
 __device__ __forceinline__ float e4m3_decode(uint32_t packed) {
-#if defined(ECO_HW_FP8_DECODE)
   return __builtin_amdgcn_cvt_f32_fp8((int)packed, SEL);
-#else
-  const uint32_t c = (packed >> (8 * SEL)) & 0xFFu;
-  const float mag = u2f((c & 0x7Fu) << 20) * 0x1p120f;
-  return u2f(f2u(mag) | ((c & 0x80u) << 24));
-#endif
 }
+
+// Correctly rounded fp32 square root for 2^-96 <= x <= 2^96: the hardware estimate (1 ulp) followed
+// by the two-sided residual test that picks the neighbour when the estimate is on the wrong side
+// of a rounding boundary.  It is the standard correctly-rounded sequence without the input scaling
+// and special-value handling that only matter outside that range; sqrtf() covers the rest.
+__device__ __forceinline__ float sqrt_rn_midrange(float x) {
+  float y = __builtin_amdgcn_sqrtf(x);
+  const float ydn = u2f(f2u(y) - 1u), yup = u2f(f2u(y) + 1u);
+  const float rdn = fmaf(-ydn, y, x), rup = fmaf(-yup, y, x);
+  y = rdn <= 0.0f ? ydn : y;
+  y = rup > 0.0f ? yup : y;
+  return y;
+}
+constexpr uint32_t SQRT_MID_LO = 0x0F800000u;   // 2^-96
+constexpr uint32_t SQRT_MID_HI = 0x6F800000u;   // 2^96
 
 // Position of |y| on the E4M3 code axis, in units of 2^-20 codes: codes are linear in the fp32
 // bit pattern above 2^-6 (three mantissa bits kept, twenty dropped) and linear in the value
@@ -48,25 +56,32 @@ __device__ __forceinline__ float e4m3_decode(uint32_t packed) {
 // onto multiples of 2^-29.
 constexpr uint32_t E4M3_MIN_NORMAL_BITS = 0x3C800000u;     // fp32 bit pattern of 2^-6
 
-// NORMAL_ONLY: the caller guarantees |y| >= 2^-6 (the common case, decided once per wave).
+// Magnitude code (0..126) of |y|.  NORMAL_ONLY: the caller guarantees |y| >= 2^-6 (the common
+// case, decided once per wave).  ay must be non-negative.
 template <int ROUND, bool NORMAL_ONLY>
-__device__ __forceinline__ uint32_t e4m3_encode(float y, uint32_t r16) {
-  const uint32_t b = f2u(y) & 0x7FFFFFFFu;
+__device__ __forceinline__ uint32_t e4m3_encode_mag(float ay, uint32_t r16) {
+  const uint32_t b = f2u(ay);
   uint32_t mag;
   if (ROUND == ROUND_SR) {
     uint32_t axis = b - 0x3C000000u;                        // code 8 <-> 0x3C800000
-    if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = f2u(u2f(b) + 0x1p-6f) - 0x3C800000u;
+    if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = f2u(ay + 0x1p-6f) - 0x3C800000u;
     mag = (axis + (r16 << 4)) >> 20;                        // up iff frac20 + 16*r16 >= 2^20
   } else {
     if (NORMAL_ONLY || b >= E4M3_MIN_NORMAL_BITS) {
       const uint32_t k = b - 0x3C000000u;
       mag = (k + 0x7FFFFu + ((k >> 20) & 1u)) >> 20;        // nearest, ties to the even code
     } else {
-      mag = f2u(u2f(b) + 0x1p14f) - 0x46800000u;            // ulp(2^14) = 2^-9: exact nearest-even
+      mag = f2u(ay + 0x1p14f) - 0x46800000u;                // ulp(2^14) = 2^-9: exact nearest-even
     }
   }
-  mag = mag < 126u ? mag : 126u;                            // saturate at 448 (0x7E)
-  return mag | ((f2u(y) >> 24) & 0x80u);
+  return mag < 126u ? mag : 126u;                           // saturate at 448 (0x7E)
+}
+
+// Sign bits of four fp32 values as a dword of code sign bits: byte j = 0x80 if x_j is negative.
+__device__ __forceinline__ uint32_t sign_bytes4(float x0, float x1, float x2, float x3) {
+  const uint32_t lo = __builtin_amdgcn_perm(f2u(x1), f2u(x0), 0x0c0c0703u);   // bytes: x0.b3, x1.b3, 0, 0
+  const uint32_t hi = __builtin_amdgcn_perm(f2u(x3), f2u(x2), 0x07030c0cu);   // bytes: 0, 0, x2.b3, x3.b3
+  return (lo | hi) & 0x80808080u;
 }
 
 // ---------------------------------------------------------------------------------- INT4
@@ -75,9 +90,10 @@ __device__ __forceinline__ float int4_decode(uint32_t packed, int idx) {
   return (float)v;
 }
 
+// Two's-complement nibble of round(y) in [-7, 7].
 template <int ROUND>
 __device__ __forceinline__ uint32_t int4_encode(float y, uint32_t r16) {
-  const float ay = u2f(f2u(y) & 0x7FFFFFFFu);
+  const float ay = __builtin_fabsf(y);
   uint32_t mag;
   if (ROUND == ROUND_SR) {
     // ulp(8.0) = 2^-20: the addition rounds |y| to nearest-even multiples of 2^-20
@@ -88,8 +104,8 @@ __device__ __forceinline__ uint32_t int4_encode(float y, uint32_t r16) {
     mag = f2u(ay + 0x1p23f) - 0x4B000000u;                  // ulp(2^23) = 1: exact nearest-even
   }
   mag = mag < 7u ? mag : 7u;
-  const uint32_t neg = f2u(y) >> 31;
-  return (neg ? (0u - mag) : mag) & 15u;
+  const uint32_t sgn = (uint32_t)((int32_t)f2u(y) >> 31);   // all ones if negative
+  return ((mag ^ sgn) - sgn) & 15u;
 }
 
 // ---------------------------------------------------------------------------------- Philox4x32-10

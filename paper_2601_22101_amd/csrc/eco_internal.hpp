@@ -19,7 +19,7 @@ struct TensorDesc {          // 64 bytes, device table entry
   void *m;
   void *v;
   uint64_t numel;
-  uint32_t first_tile;       // index of this tensor's first tile in the group's tile list
+  uint32_t first_tile;       // index of this tensor's first full tile in the group's tile list
   uint32_t tensor_id;
   uint64_t pad;
 };
@@ -27,8 +27,10 @@ static_assert(sizeof(TensorDesc) == 64, "TensorDesc layout");
 
 struct StepArgs {            // by-value kernel argument: everything wave-uniform
   const TensorDesc *tensors;
-  const uint32_t *tile_tensor;   // tile -> index into tensors
-  uint32_t num_tiles;
+  const uint32_t *tile_tensor;   // full tile -> index into tensors
+  const uint32_t *ragged_tensor; // tensors that end in a partial tile
+  uint32_t num_tiles;            // full tiles
+  uint32_t num_ragged;
   uint32_t bs_shift;             // log2(block_size)
   float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd;
   uint32_t seed_lo, seed_hi, step_lo;

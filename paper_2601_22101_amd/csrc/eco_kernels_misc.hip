@@ -47,15 +47,27 @@ __global__ __launch_bounds__(WG_THREADS) void eco_plain_kernel(const StepArgs a)
   for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
     const TensorDesc td = load_tensor_desc(a, load_tile_tensor(a, tile));
     const uint64_t tile_off = (uint64_t)(tile - td.first_tile) * TILE_ELEMS;
-    const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-    if (tile_off + TILE_ELEMS <= td.numel) plain_tile<FMT, STATE_BF16, OPT, true>(a, td, e0);
-    else plain_tile<FMT, STATE_BF16, OPT, false>(a, td, e0);
+    plain_tile<FMT, STATE_BF16, OPT, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
   }
 }
 
+template <int FMT, bool STATE_BF16, int OPT>
+__global__ __launch_bounds__(WG_THREADS) void eco_plain_ragged_kernel(const StepArgs a) {
+  const ECO_CONST_AS uint32_t *rt = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.ragged_tensor;
+  const TensorDesc td = load_tensor_desc(a, rt[blockIdx.x]);
+  const uint64_t tile_off = td.numel / TILE_ELEMS * TILE_ELEMS;
+  plain_tile<FMT, STATE_BF16, OPT, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+}
+
 hipError_t launch_step_plain(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(F, ST, OP) \
-  hipLaunchKernelGGL((eco_plain_kernel<F, ST, OP>), dim3(grid), dim3(WG_THREADS), 0, stream, args)
+#define ECO_LAUNCH(F, ST, OP)                                                                                  \
+  do {                                                                                                         \
+    if (args.num_tiles)                                                                                        \
+      hipLaunchKernelGGL((eco_plain_kernel<F, ST, OP>), dim3(grid), dim3(WG_THREADS), 0, stream, args);        \
+    if (args.num_ragged)                                                                                       \
+      hipLaunchKernelGGL((eco_plain_ragged_kernel<F, ST, OP>), dim3(args.num_ragged), dim3(WG_THREADS), 0,     \
+                         stream, args);                                                                        \
+  } while (0)
   const int key = (kv.fmt == FMT_FP32_ID ? 4 : 0) | (kv.state_bf16 ? 2 : 0) | (kv.opt == OPT_SGDM ? 1 : 0);
   switch (key) {
     case 0: ECO_LAUNCH(FMT_BF16_PLAIN, false, OPT_ADAM); break;
@@ -89,21 +101,12 @@ __device__ __forceinline__ void quantize_tile(const void *src, uint64_t numel, u
   }
   float x[8];
   load_state8<SRC_BF16, FULL>(src, e0, nvalid, x);
-  uint32_t amax = 0;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint32_t ab = f2u(x[j]) & 0x7FFFFFFFu;
-    amax = amax > ab ? amax : ab;
-  }
-  amax = group_umax(amax, 1 << (bs_shift - 3));
+  const float amax = u2f(group_umax(f2u(absmax8(x)), 1 << (bs_shift - 3)));
   float s_new, inv;
   block_scale<FMT, SCALE_BF16>(amax, s_new, inv);
-  float y[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) y[j] = x[j] * inv;
   uint32_t c[2];
   const Philox4 none = {0, 0, 0, 0};
-  encode8<FMT, ROUND_RTN, false>(y, none, c);
+  encode8<FMT, ROUND_RTN, false>(x, inv, none, c);
   store_codes8<FMT, FULL>(weights, e0, nvalid, c);
   const uint64_t blk = e0 >> bs_shift;
   const uint32_t lanes_mask = (1u << (bs_shift - 3)) - 1u;

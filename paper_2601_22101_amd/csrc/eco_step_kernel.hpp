@@ -144,11 +144,10 @@ __device__ __forceinline__ float load_scale(const void *scales, uint64_t blk) {
   return static_cast<const float *>(scales)[blk];
 }
 
-// abs-max scale of a block from the bit pattern of max|x| (wave-uniform within the block's lanes)
+// abs-max scale of a block from a = max|x| (identical in all lanes of the block)
 template <int FMT, bool SCALE_BF16>
-__device__ __forceinline__ void block_scale(uint32_t amax_bits, float &s_new, float &inv) {
+__device__ __forceinline__ void block_scale(float a, float &s_new, float &inv) {
   constexpr float RHO = FmtTraits<FMT>::RHO;
-  const float a = u2f(amax_bits);
   s_new = a / RHO;
   if (SCALE_BF16) {
     s_new = u2f(f32_to_bf16_rne(s_new) << 16);
@@ -159,16 +158,53 @@ __device__ __forceinline__ void block_scale(uint32_t amax_bits, float &s_new, fl
   if (!(inv < __builtin_inff())) { s_new = 0.0f; inv = 0.0f; }   // a == 0, or rho/a overflows
 }
 
-// Encode 8 values y = x*inv onto the grid; returns packed codes.  r[4] = the lane's Philox words.
+__device__ __forceinline__ float absmax8(const float (&x)[8]) {
+  float a = __builtin_fmaxf(__builtin_fabsf(x[0]), __builtin_fabsf(x[1]));
+#pragma unroll
+  for (int j = 2; j < 8; ++j) a = __builtin_fmaxf(a, __builtin_fabsf(x[j]));
+  return a;
+}
+
+__device__ __forceinline__ float absmin8(const float (&x)[8]) {
+  float a = __builtin_fminf(__builtin_fabsf(x[0]), __builtin_fabsf(x[1]));
+#pragma unroll
+  for (int j = 2; j < 8; ++j) a = __builtin_fminf(a, __builtin_fabsf(x[j]));
+  return a;
+}
+
+// Encode y_j = x_j * inv (j = 0..7) onto the grid; returns packed codes.  r = the lane's Philox words.
 template <int FMT, int ROUND, bool NORMAL_ONLY>
-__device__ __forceinline__ void encode8(const float (&y)[8], const Philox4 &r, uint32_t (&c)[2]) {
+__device__ __forceinline__ void encode8(const float (&x)[8], float inv, const Philox4 &r, uint32_t (&c)[2]) {
   const uint32_t rw[4] = {r.w0, r.w1, r.w2, r.w3};
   c[0] = 0; c[1] = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-    if (FMT == FMT_FP8) c[j >> 2] |= e4m3_encode<ROUND, NORMAL_ONLY>(y[j], r16) << (8 * (j & 3));
-    else c[0] |= int4_encode<ROUND>(y[j], r16) << (4 * j);
+    if (FMT == FMT_FP8) c[j >> 2] |= e4m3_encode_mag<ROUND, NORMAL_ONLY>(__builtin_fabsf(x[j]) * inv, r16) << (8 * (j & 3));
+    else c[0] |= int4_encode<ROUND>(x[j] * inv, r16) << (4 * j);
+  }
+  if (FMT == FMT_FP8) {   // inv >= 0, so the sign of y is the sign of x
+    c[0] |= sign_bytes4(x[0], x[1], x[2], x[3]);
+    c[1] |= sign_bytes4(x[4], x[5], x[6], x[7]);
+  }
+}
+
+// d_j = sqrt(x_j) + eps for eight non-negative x.  When every x of the wave lies in the range of
+// sqrt_rn_midrange the short sequence is used; both branches return the correctly rounded root.
+__device__ __forceinline__ void sqrt_plus_eps8(const float (&x)[8], float eps, float (&d)[8]) {
+  uint32_t lo = f2u(x[0]), hi = f2u(x[0]);
+#pragma unroll
+  for (int j = 1; j < 8; ++j) {
+    const uint32_t b = f2u(x[j]);
+    lo = lo < b ? lo : b;
+    hi = hi > b ? hi : b;
+  }
+  if (__all(lo >= SQRT_MID_LO && hi <= SQRT_MID_HI)) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) d[j] = sqrt_rn_midrange(x[j]) + eps;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) d[j] = sqrtf(x[j]) + eps;
   }
 }
 
@@ -196,41 +232,38 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
 
   // OPTIM_STEP on the de-quantized weights
   float th[8], d[8];
-  uint32_t amax = 0;
+  if (OPT == OPT_ADAM) {
+    float x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
+      v[j] = fmaf(a.b2, v[j], a.omb2 * (g[j] * g[j]));
+      x[j] = v[j] * a.rbc2;
+    }
+    store_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);   // v is final (Alg. 3 returns it unchanged)
+    sqrt_plus_eps8(x, a.eps, d);
+  }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     float wj = w[j] * s_old;
-    m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
     float u;
     if (OPT == OPT_ADAM) {
-      v[j] = fmaf(a.b2, v[j], a.omb2 * (g[j] * g[j]));
-      d[j] = sqrtf(v[j] * a.rbc2) + a.eps;
       u = (a.c1 * m[j]) / d[j];
     } else {
+      m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
       d[j] = 0.0f;
       u = a.lr * m[j];
     }
     if (a.wd != 0.0f) wj = wj - a.wd * wj;
     th[j] = wj - u;
     if (!FULL && j >= nvalid) th[j] = 0.0f;
-    const uint32_t ab = f2u(th[j]) & 0x7FFFFFFFu;
-    amax = amax > ab ? amax : ab;
   }
-  if (OPT == OPT_ADAM) store_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);   // v is final (Alg. 3 returns it unchanged)
 
   // ECO_QUANTIZE
-  amax = group_umax(amax, 1 << (a.bs_shift - 3));
+  const float amax = u2f(group_umax(f2u(absmax8(th)), 1 << (a.bs_shift - 3)));
   float s_new, inv;
   block_scale<FMT, SCALE_BF16>(amax, s_new, inv);
 
-  float y[8];
-  uint32_t ymin = 0xFFFFFFFFu;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    y[j] = th[j] * inv;
-    const uint32_t yb = f2u(y[j]) & 0x7FFFFFFFu;
-    ymin = ymin < yb ? ymin : yb;
-  }
   Philox4 r = {0, 0, 0, 0};
   if (ROUND == ROUND_SR) {
     const uint64_t q = e0 >> 3;
@@ -239,10 +272,11 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
   uint32_t cn[2];
   if (FMT == FMT_FP8) {
     // the E4M3 subnormal range (|y| < 2^-6) needs a second formula; it is rare, so decide per wave
-    if (__any(ymin < E4M3_MIN_NORMAL_BITS)) encode8<FMT, ROUND, false>(y, r, cn);
-    else encode8<FMT, ROUND, true>(y, r, cn);
+    // (multiplication by inv >= 0 is monotone, so the smallest |y| is fl(min|theta~| * inv))
+    if (__any(absmin8(th) * inv < 0x1p-6f)) encode8<FMT, ROUND, false>(th, inv, r, cn);
+    else encode8<FMT, ROUND, true>(th, inv, r, cn);
   } else {
-    encode8<FMT, ROUND, true>(y, r, cn);
+    encode8<FMT, ROUND, true>(th, inv, r, cn);
   }
   store_codes8<FMT, FULL>(td.w, e0, nvalid, cn);
 
@@ -292,24 +326,39 @@ __device__ __forceinline__ TensorDesc load_tensor_desc(const StepArgs &a, uint32
   return td;
 }
 
-// Persistent kernel: workgroup b handles tiles b, b + gridDim.x, ...  The tile -> tensor table and
-// the tensor descriptors are wave-uniform and are fetched with scalar loads.
+// Persistent kernel over the full tiles: workgroup b handles tiles b, b + gridDim.x, ...  The
+// tile -> tensor table and the tensor descriptors are wave-uniform and are fetched with scalar loads.
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int OPT, int ROUND>
-__global__ __launch_bounds__(WG_THREADS) void eco_step_kernel(const StepArgs a) {
+__global__ __launch_bounds__(WG_THREADS, 8) void eco_step_kernel(const StepArgs a) {
   for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
     const TensorDesc td = load_tensor_desc(a, load_tile_tensor(a, tile));
     const uint64_t tile_off = (uint64_t)(tile - td.first_tile) * TILE_ELEMS;
-    const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-    if (tile_off + TILE_ELEMS <= td.numel) step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, true>(a, td, e0);
-    else step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, false>(a, td, e0);
+    step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
   }
+}
+
+// The last, partial tile of each tensor whose length is not a multiple of TILE_ELEMS: one workgroup
+// per such tensor, element-wise guarded accesses.  A separate kernel keeps the guards' registers and
+// branches out of the full-tile kernel.
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int OPT, int ROUND>
+__global__ __launch_bounds__(WG_THREADS) void eco_step_ragged_kernel(const StepArgs a) {
+  const ECO_CONST_AS uint32_t *rt = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.ragged_tensor;
+  const TensorDesc td = load_tensor_desc(a, rt[blockIdx.x]);
+  const uint64_t tile_off = td.numel / TILE_ELEMS * TILE_ELEMS;
+  step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
 }
 
 template <int FMT, bool STATE_BF16>
 hipError_t launch_step_variants(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(SC, OP, RD)                                                                          \
-  hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(grid), dim3(WG_THREADS), 0,   \
-                     stream, args)
+#define ECO_LAUNCH(SC, OP, RD)                                                                              \
+  do {                                                                                                      \
+    if (args.num_tiles)                                                                                     \
+      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(grid), dim3(WG_THREADS), 0,   \
+                         stream, args);                                                                     \
+    if (args.num_ragged)                                                                                    \
+      hipLaunchKernelGGL((eco_step_ragged_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(args.num_ragged),      \
+                         dim3(WG_THREADS), 0, stream, args);                                                \
+  } while (0)
   const int key = (kv.scale_bf16 ? 4 : 0) | (kv.opt == OPT_SGDM ? 2 : 0) | (kv.round == ROUND_RTN ? 1 : 0);
   switch (key) {
     case 0: ECO_LAUNCH(false, OPT_ADAM, ROUND_SR); break;

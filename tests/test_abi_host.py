@@ -111,7 +111,7 @@ def test_flat_helpers_validate(eco):
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 0, 0x1000, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 16, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_set_option, 5, 1) == eco.ECO_EINVAL
-    assert _status(eco, eco.eco_set_option, 0, 1000) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_set_option, 0, 100000) == eco.ECO_EINVAL
     eco.eco_set_option(0, 0)
 
 
