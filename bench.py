@@ -45,7 +45,23 @@ def algorithmic_bytes(wl) -> float:
     return total
 
 
-def cpu_baseline(wl, target_seconds: float = 12.0) -> dict:
+def profiled_traffic(wl_name: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy of known
+    size) for this workload, as recorded in the committed profile summary; None if there is no such record."""
+    tag = {"cfg4_smoe_2p1b_shaped": "fp8_cfg4"}.get(wl_name)
+    if not tag:
+        return None
+    path = os.path.join(ROOT, "profiles", f"eco_step_kernel_{tag}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(wl, target_seconds: float = 10.0) -> dict:
     """The CPU oracle, as it stands, timed on a bounded sample of the same workload (host cores of this machine)."""
     import numpy as np
 
@@ -88,7 +104,7 @@ def cpu_baseline(wl, target_seconds: float = 12.0) -> dict:
             break
     n0, dt0 = run(prepare(probe_ids))
     rate = n0 / dt0
-    want = rate * target_seconds
+    want = min(rate * target_seconds, 6.0e8)          # also bounds the time spent preparing host inputs
     ids, acc = [], 0
     for i in quant:
         if acc >= want and ids:
@@ -110,7 +126,14 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="workload number (1-5) of the baseline's configs")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning: workgroups per compute unit (0 = default)")
+    ap.add_argument("--lds-bytes", type=int, default=-1, help="launch tuning: dynamic LDS per workgroup (-1 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--bulk-grad", action="store_true",
+                    help="draw each step's gradients with a few generator calls over the whole arena instead of one "
+                         "per tensor (same distribution; for runs under rocprofv3 --pmc)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed steps, run two plain 1 GiB device copies (a reference of known size for "
+                         "scaling rocprofv3 byte counters)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -129,6 +152,8 @@ def main() -> int:
         return 1
     if args.wgs_per_cu:
         eco.eco_set_option(0, args.wgs_per_cu)
+    if args.lds_bytes >= 0:
+        eco.eco_set_option(1, args.lds_bytes)
 
     wl = workloads.CONFIGS[args.config]()
     t_setup = time.perf_counter()
@@ -137,17 +162,18 @@ def main() -> int:
     print(f"[bench] {wl.name}: {len(wl.tensors)} tensors, {wl.numel} parameters, set-up {time.perf_counter() - t_setup:.1f} s",
           file=sys.stderr, flush=True)
 
+    fill = dw.fill_gradients_bulk if args.bulk_grad else dw.fill_gradients
     k = 0
     for _ in range(args.warmup):
         k += 1
-        dw.fill_gradients(k)
+        fill(k)
         dw.step(k)
     torch.cuda.synchronize()
 
     wall, kernel_ms = 0.0, []
     for _ in range(args.steps):
         k += 1
-        dw.fill_gradients(k)                      # fresh gradients, outside the timed region
+        fill(k)                                   # fresh gradients, outside the timed region
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -173,12 +199,19 @@ def main() -> int:
                    if args.config != 5 else "int4 codes, group-128 bf16 scales, bf16 gradients, bf16 m and v",
                    "optimizer": "Adam-ECO, stochastic rounding", "launches_per_step": 1 if args.config != 2 else 2},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": profiled_traffic(wl.name),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": avg_kernel_s * 1e3},
     }
     dw.close()
     del dw
     torch.cuda.empty_cache()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)

@@ -124,7 +124,7 @@ typedef struct eco_plan eco_plan_t;
  *   layout     : HOST; only block_size, state_dtype, scale_dtype and opt are read (they fix the memory
  *                layout the descriptors are checked against)
  *   out        : receives the plan; owned by the library until eco_plan_destroy
- * Allocates device memory for the tables (about 64 bytes per tensor + 4 bytes per 2048 elements) and
+ * Allocates device memory for the tables (about 64 bytes per tensor + 4 bytes per 512 elements) and
  * copies them synchronously.  Errors: ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_ENOMEM, ECO_EHIP.
  */
 eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *layout, eco_plan_t **out);
@@ -171,8 +171,11 @@ eco_status_t eco_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, u
 /* eco_step_constants — host only: validates hp as eco_step does and writes the derived fp32 constants. */
 eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out);
 
-/* Launch tuning, host only.  option 0: workgroups per compute unit of the persistent step kernel
- * (0 = library default).  Does not change results. */
+/* Launch tuning, host only; never changes results.
+ *   option 0: cap on the step kernel's grid, in workgroups per compute unit; the kernel then loops over
+ *             tiles (0 = library default: one workgroup per 512-element tile, no cap)
+ *   option 1: bytes of dynamic LDS requested per workgroup of the step kernel (-1 = library default).
+ *             The kernel never touches it; the request only caps resident workgroups per compute unit. */
 eco_status_t eco_set_option(int32_t option, int64_t value);
 
 const char *eco_status_string(eco_status_t status);

@@ -12,7 +12,7 @@ from dataclasses import dataclass
 from typing import Iterable, List, Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libeco.so")
+LIB_PATH = os.environ.get("ECO_LIB_PATH") or os.path.join(_HERE, "libeco.so")   # override: a tuning variant
 
 ECO_OK, ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_EHIP, ECO_ENOMEM = 0, -1, -2, -3, -4, -5
 ECO_FMT_FP8_E4M3, ECO_FMT_INT4, ECO_FMT_BF16_PLAIN, ECO_FMT_FP32_IDENTITY = 0, 1, 2, 3

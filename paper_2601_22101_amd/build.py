@@ -63,16 +63,28 @@ def _compile(src: str, force: bool, extra) -> str:
     return obj
 
 
-def build(force: bool = False, save_temps: bool = False, jobs: int = 6) -> str:
+def build(force: bool = False, jobs: int = 6, defines=(), out: str = LIB) -> str:
+    """Compile every source and link `out`.  `defines` (e.g. ["ECO_WG_THREADS=256"]) builds a tuning
+    variant: give it its own `out`, objects then go to a directory of their own."""
+    global BUILD
+    if defines:
+        BUILD = os.path.join(HERE, "_build", "variant_" + "_".join(d.replace("=", "-") for d in defines))
+        force = force or not os.path.exists(out)
     os.makedirs(BUILD, exist_ok=True)
-    extra = ["-save-temps=obj"] if save_temps else []
+    extra = [f"-D{d}" for d in defines]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force, extra), SOURCES))
-    if force or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
-        cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    if force or not os.path.exists(out) or any(os.path.getmtime(o) > os.path.getmtime(out) for o in objs):
+        cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out]
         subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv, save_temps="--save-temps" in sys.argv))
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--force", action="store_true")
+    ap.add_argument("--define", action="append", default=[])
+    ap.add_argument("--out", default=LIB)
+    a = ap.parse_args()
+    print(build(force=a.force, defines=a.define, out=a.out))

@@ -17,6 +17,7 @@ namespace {
 
 thread_local std::string g_last_error;
 int64_t g_wgs_per_cu = 0;   // 0 = default
+int64_t g_lds_bytes = -1;    // -1 = default; dynamic LDS per workgroup of the step kernel (occupancy limiter)
 
 eco_status_t fail(eco_status_t st, const char *fmt, ...) {
   char buf[512];
@@ -108,10 +109,16 @@ int num_compute_units() {
   return cus;
 }
 
+// Default: one workgroup per tile.  The hardware dispatcher then hands out tiles in address order,
+// which keeps the set of DRAM pages in flight compact; grid-stride loops over a resident grid
+// measured 10-15 % slower on MI355X.  Option 0 overrides with a resident grid.
 unsigned grid_for(uint64_t tiles, int cus) {
-  const int64_t per_cu = g_wgs_per_cu > 0 ? g_wgs_per_cu : 8;
-  uint64_t g = static_cast<uint64_t>(cus) * static_cast<uint64_t>(per_cu);
-  if (g > tiles) g = tiles;
+  uint64_t g = tiles;
+  if (g_wgs_per_cu > 0) {
+    const uint64_t cap = static_cast<uint64_t>(cus) * static_cast<uint64_t>(g_wgs_per_cu);
+    if (g > cap) g = cap;
+  }
+  if (g > 0x7FFFFFFFull) g = 0x7FFFFFFFull;
   if (g == 0) g = 1;
   return static_cast<unsigned>(g);
 }
@@ -145,10 +152,17 @@ const char *eco_last_error(void) { return g_last_error.c_str(); }
 int eco_version(void) { return 100; }
 
 eco_status_t eco_set_option(int32_t option, int64_t value) {
-  if (option != 0) return fail(ECO_EINVAL, "unknown option %d", option);
-  if (value < 0 || value > 65536) return fail(ECO_EINVAL, "workgroups per compute unit must lie in [0, 65536]");
-  g_wgs_per_cu = value;
-  return ECO_OK;
+  if (option == 0) {
+    if (value < 0 || value > 65536) return fail(ECO_EINVAL, "workgroups per compute unit must lie in [0, 65536]");
+    g_wgs_per_cu = value;
+    return ECO_OK;
+  }
+  if (option == 1) {
+    if (value < -1 || value > 65536) return fail(ECO_EINVAL, "LDS bytes per workgroup must lie in [-1, 65536]");
+    g_lds_bytes = value;
+    return ECO_OK;
+  }
+  return fail(ECO_EINVAL, "unknown option %d", option);
 }
 
 eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out) {
@@ -272,6 +286,7 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     a.seed_lo = static_cast<uint32_t>(hp->seed);
     a.seed_hi = static_cast<uint32_t>(hp->seed >> 32);
     a.step_lo = static_cast<uint32_t>(hp->step);
+    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes) : eco::DEFAULT_STEP_LDS_BYTES;
     eco::KernelVariant kv;
     kv.fmt = f;
     kv.state_bf16 = hp->state_dtype == ECO_DT_BF16;

@@ -5,12 +5,21 @@
 
 namespace eco {
 
-// A tile is TILE_ELEMS consecutive elements of one tensor; a 256-thread workgroup processes one
-// tile per loop iteration, 8 consecutive elements per lane.  A scale group of B elements
-// therefore occupies B/8 consecutive lanes (B = 32..512 fits inside one 64-lane wave).
-constexpr int TILE_ELEMS = 2048;
-constexpr int WG_THREADS = 256;
+// A tile is TILE_ELEMS consecutive elements of one tensor, processed by one workgroup of one wave,
+// 8 consecutive elements per lane.  A scale group of B elements therefore occupies B/8 consecutive
+// lanes (B = 32..512 fits inside the 64-lane wave).
+#ifndef ECO_WG_THREADS
+#define ECO_WG_THREADS 64
+#endif
+constexpr int WG_THREADS = ECO_WG_THREADS;
 constexpr int ELEMS_PER_LANE = 8;
+constexpr int TILE_ELEMS = WG_THREADS * ELEMS_PER_LANE;
+// Dynamic LDS requested per workgroup of the full-tile step kernel.  The kernel does not touch it:
+// the request only caps how many waves a compute unit (160 KB of LDS) holds at once.  The step is
+// bound by HBM, and on MI355X the memory system delivers most when about 12 waves per compute
+// unit have their 5.6 KB of loads in flight; with more resident waves the achieved bandwidth
+// drops (measured: 32 waves 5.2 TB/s, 12 waves 5.7 TB/s, 8 waves 5.1 TB/s).
+constexpr uint32_t DEFAULT_STEP_LDS_BYTES = 13312;
 
 struct TensorDesc {          // 64 bytes, device table entry
   void *w;                   // weights / codes
@@ -34,6 +43,7 @@ struct StepArgs {            // by-value kernel argument: everything wave-unifor
   uint32_t bs_shift;             // log2(block_size)
   float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd;
   uint32_t seed_lo, seed_hi, step_lo;
+  uint32_t lds_bytes;            // host side only: dynamic LDS per workgroup of the step kernel
 };
 
 struct KernelVariant {

@@ -353,8 +353,8 @@ hipError_t launch_step_variants(const KernelVariant &kv, const StepArgs &args, u
 #define ECO_LAUNCH(SC, OP, RD)                                                                              \
   do {                                                                                                      \
     if (args.num_tiles)                                                                                     \
-      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(grid), dim3(WG_THREADS), 0,   \
-                         stream, args);                                                                     \
+      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(grid), dim3(WG_THREADS),      \
+                         args.lds_bytes, stream, args);                                                     \
     if (args.num_ragged)                                                                                    \
       hipLaunchKernelGGL((eco_step_ragged_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(args.num_ragged),      \
                          dim3(WG_THREADS), 0, stream, args);                                                \

@@ -130,6 +130,30 @@ class DeviceWorkload:
         for tv in self.tensors:
             workloads.gradient(self.wl, tv.tensor_id, step, device=self.device, base_seed=self.base_seed, out=tv.grad)
 
+    def fill_gradients_bulk(self, step: int) -> None:
+        """Same distribution as fill_gradients, drawn with a handful of generator calls over the whole
+        gradient arena instead of one per tensor (other values, far fewer launches): for runs under
+        a counter-collecting profiler, where every launch is expensive."""
+        wl = self.wl
+        g = torch.Generator(device=self.device)
+        g.manual_seed(workloads._mix(self.base_seed, 0x6B, step))
+        chunk = 1 << 28
+        stds = {tv.spec.grad_std for tv in self.tensors}
+        common = stds.pop() if len(stds) == 1 else 1.0
+        for o in range(0, self.grad.numel(), chunk):
+            n = min(chunk, self.grad.numel() - o)
+            x = torch.randn(n, generator=g, device=self.device, dtype=torch.float32)
+            if common != 1.0:
+                x.mul_(common)
+            self.grad[o:o + n].copy_(x)          # fp32 -> bf16: reads 4n bytes, writes 2n bytes
+        if stds:
+            for tv in self.tensors:
+                tv.grad.mul_(tv.spec.grad_std)
+        for tv in self.tensors:
+            t = tv.spec
+            if t.expert >= 0 and t.expert in workloads.inactive_experts(wl, step, t.layer, self.base_seed):
+                tv.grad.zero_()
+
     def step(self, step: int, **over) -> None:
         self.plan.step(self.hparams(step, **over))
 
