@@ -127,6 +127,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="workload number (1-5) of the baseline's configs")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning: workgroups per compute unit (0 = default)")
     ap.add_argument("--lds-bytes", type=int, default=-1, help="launch tuning: dynamic LDS per workgroup (-1 = default)")
+    ap.add_argument("--variant", default="adam-sr", choices=["adam-sr", "adam-rtn", "sgdm-sr", "sgdm-rtn"],
+                    help="optimizer / rounding variant of the step (the headline metric is adam-sr)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
@@ -156,8 +158,16 @@ def main() -> int:
         eco.eco_set_option(1, args.lds_bytes)
 
     wl = workloads.CONFIGS[args.config]()
+    over = {}
+    if args.variant.startswith("sgdm"):
+        over["opt"] = eco.ECO_OPT_SGDM
+    if args.variant.endswith("rtn"):
+        over["round"] = eco.ECO_ROUND_RTN
     t_setup = time.perf_counter()
     dw = harness.DeviceWorkload(wl, "cuda:0")
+    if "opt" in over:
+        dw.plan.close()
+        dw.plan = eco.Plan([dw.descriptor(tv) for tv in dw.tensors], dw.hparams(1, **over))
     torch.cuda.synchronize()
     print(f"[bench] {wl.name}: {len(wl.tensors)} tensors, {wl.numel} parameters, set-up {time.perf_counter() - t_setup:.1f} s",
           file=sys.stderr, flush=True)
@@ -167,7 +177,7 @@ def main() -> int:
     for _ in range(args.warmup):
         k += 1
         fill(k)
-        dw.step(k)
+        dw.step(k, **over)
     torch.cuda.synchronize()
 
     wall, kernel_ms = 0.0, []
@@ -178,7 +188,7 @@ def main() -> int:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record()
-        dw.step(k)
+        dw.step(k, **over)
         e1.record()
         torch.cuda.synchronize()
         wall += time.perf_counter() - t0
@@ -197,7 +207,8 @@ def main() -> int:
         "config": {"workload": wl.name, "tensors": len(wl.tensors), "parameters": wl.numel,
                    "format": "fp8_e4m3 codes, block-128 fp32 scales, bf16 gradients, fp32 m and v"
                    if args.config != 5 else "int4 codes, group-128 bf16 scales, bf16 gradients, bf16 m and v",
-                   "optimizer": "Adam-ECO, stochastic rounding", "launches_per_step": 1 if args.config != 2 else 2},
+                   "optimizer": {"adam-sr": "Adam-ECO, stochastic rounding", "adam-rtn": "Adam-ECO, round to nearest",
+                                 "sgdm-sr": "SGDM-ECO, stochastic rounding", "sgdm-rtn": "SGDM-ECO, round to nearest"}[args.variant], "launches_per_step": 1 if args.config != 2 else 2},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": profiled_traffic(wl.name),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": avg_kernel_s * 1e3},

@@ -286,7 +286,10 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     a.seed_lo = static_cast<uint32_t>(hp->seed);
     a.seed_hi = static_cast<uint32_t>(hp->seed >> 32);
     a.step_lo = static_cast<uint32_t>(hp->step);
-    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes) : eco::DEFAULT_STEP_LDS_BYTES;
+    // fp32 state: 20 B per parameter, bound by HBM -> cap the resident waves; bf16 state: 11-12 B per
+    // parameter, bound by vector-ALU issue -> full occupancy
+    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes)
+                                   : (hp->state_dtype == ECO_DT_FP32 ? eco::DEFAULT_STEP_LDS_BYTES : 0u);
     eco::KernelVariant kv;
     kv.fmt = f;
     kv.state_bf16 = hp->state_dtype == ECO_DT_BF16;

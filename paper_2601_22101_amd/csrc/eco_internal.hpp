@@ -18,7 +18,8 @@ constexpr int TILE_ELEMS = WG_THREADS * ELEMS_PER_LANE;
 // the request only caps how many waves a compute unit (160 KB of LDS) holds at once.  The step is
 // bound by HBM, and on MI355X the memory system delivers most when about 12 waves per compute
 // unit have their 5.6 KB of loads in flight; with more resident waves the achieved bandwidth
-// drops (measured: 32 waves 5.2 TB/s, 12 waves 5.7 TB/s, 8 waves 5.1 TB/s).
+// drops (measured: 32 waves 5.2 TB/s, 12 waves 5.7 TB/s, 8 waves 5.1 TB/s).  Used for fp32 optimizer
+// state only: with bf16 state the step moves half the bytes and is bound by instruction issue.
 constexpr uint32_t DEFAULT_STEP_LDS_BYTES = 13312;
 
 struct TensorDesc {          // 64 bytes, device table entry
