@@ -25,6 +25,7 @@ _SRC = os.path.join(_HERE, "eco_oracle.c")
 FMT_E4M3, FMT_INT4, FMT_IDENTITY, FMT_ADDNOISE, FMT_BF16_PLAIN = range(5)
 OPT_ADAM, OPT_SGDM = 0, 1
 ROUND_SR, ROUND_RTN = 0, 1
+MODE_NAIVE, MODE_ECO, MODE_EXACT, MODE_MASTER = 0, 1, 2, 3
 
 
 def lib_path(real: str) -> str:
@@ -44,7 +45,7 @@ def build(force: bool = False) -> None:
 
 class _Cfg(C.Structure):
     _fields_ = [
-        ("fmt", C.c_int32), ("opt", C.c_int32), ("round", C.c_int32), ("inject", C.c_int32),
+        ("fmt", C.c_int32), ("opt", C.c_int32), ("round", C.c_int32), ("mode", C.c_int32),
         ("block_size", C.c_int32), ("state_bf16", C.c_int32), ("scale_bf16", C.c_int32), ("reserved", C.c_int32),
         ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
         ("weight_decay", C.c_double),
@@ -59,7 +60,8 @@ class StepConfig:
     fmt: int = FMT_E4M3
     opt: int = OPT_ADAM
     round: int = ROUND_SR
-    inject: bool = True
+    inject: bool = True          # False = naive master-weight removal
+    mode: int = -1               # -1: from `inject`; else MODE_NAIVE / MODE_ECO / MODE_EXACT / MODE_MASTER
     block_size: int = 128
     state_bf16: bool = False
     scale_bf16: bool = False
@@ -74,7 +76,8 @@ class StepConfig:
     tensor_id: int = 0
 
     def _c(self) -> _Cfg:
-        return _Cfg(self.fmt, self.opt, self.round, int(self.inject), self.block_size, int(self.state_bf16),
+        mode = self.mode if self.mode >= 0 else int(self.inject)
+        return _Cfg(self.fmt, self.opt, self.round, mode, self.block_size, int(self.state_bf16),
                     int(self.scale_bf16), 0, self.lr, self.beta1, self.beta2, self.eps, self.weight_decay,
                     self.step, self.seed & (2**64 - 1), self.elem_offset, self.tensor_id, 0)
 
@@ -174,13 +177,13 @@ class Oracle:
         return out
 
     def eco_step(self, cfg: StepConfig, numel, m, v=None, *, codes=None, scales=None, wreal=None,
-                 grad_bf16=None, grad_real=None, xi=None, dbg_theta=None, dbg_err=None) -> int:
+                 grad_bf16=None, grad_real=None, xi=None, aux=None, dbg_theta=None, dbg_err=None) -> int:
         """In-place step; every array must be C-contiguous and of this build's dtype
         (codes uint8, grad_bf16 uint16).  Returns the oracle's status (0 = ok)."""
         def chk(a, dt):
             if a is not None:
                 assert a.flags["C_CONTIGUOUS"] and a.dtype == dt, (a.dtype, dt)
-        for a in (scales, wreal, grad_real, m, v, xi, dbg_theta, dbg_err):
+        for a in (scales, wreal, grad_real, m, v, xi, aux, dbg_theta, dbg_err):
             chk(a, self.dtype)
         chk(codes, np.uint8)
         chk(grad_bf16, np.uint16)
@@ -188,7 +191,7 @@ class Oracle:
         R = self._creal
         return int(self.lib.oracle_eco_step(
             C.byref(c), C.c_uint64(numel), _ptr(codes, C.c_uint8), _ptr(scales, R), _ptr(wreal, R),
-            _ptr(grad_bf16, C.c_uint16), _ptr(grad_real, R), _ptr(m, R), _ptr(v, R), _ptr(xi, R),
+            _ptr(grad_bf16, C.c_uint16), _ptr(grad_real, R), _ptr(m, R), _ptr(v, R), _ptr(xi, R), _ptr(aux, R),
             _ptr(dbg_theta, R), _ptr(dbg_err, R)))
 
 

@@ -85,9 +85,10 @@ static inline REAL r_abs(REAL x) { return x < 0 ? -x : (x == 0 ? (REAL)0 : x); }
 enum { FMT_E4M3 = 0, FMT_INT4 = 1, FMT_IDENTITY = 2, FMT_ADDNOISE = 3, FMT_BF16_PLAIN = 4 };
 enum { OPT_ADAM = 0, OPT_SGDM = 1 };
 enum { ROUND_SR = 0, ROUND_RTN = 1 };
+enum { MODE_NAIVE = 0, MODE_ECO = 1, MODE_EXACT = 2, MODE_MASTER = 3 };
 
 typedef struct {
-  int32_t fmt, opt, round, inject;
+  int32_t fmt, opt, round, mode;
   int32_t block_size, state_bf16, scale_bf16, reserved;
   double lr, beta1, beta2, eps, weight_decay;
   uint64_t step, seed, elem_offset;
@@ -327,18 +328,25 @@ int oracle_dequantize(int fmt, int block_size, uint64_t numel, const uint8_t *co
  *   m, v           : optimizer state (v unused for SGDM); if cfg->state_bf16
  *                    the values written are rounded to bfloat16
  *   xi             : FMT_ADDNOISE only, q(x) = x + xi
+ *   aux            : MODE_EXACT: the stored error e_t, replaced by e_{t+1} (Appendix A, Eq. im_inject:
+ *                    m <- m~ + e_t/eta - e_{t+1}/(eta beta), SGDM only);
+ *                    MODE_MASTER: high-precision master weights (Sec. 3.1 "Quantization-Aware
+ *                    Training with Master Weights"): the update is applied to them, the quantized
+ *                    weights are q(master), and the momentum is left alone
  *   dbg_theta, dbg_err : optional outputs theta~ and e
+ * cfg->mode: MODE_NAIVE (no injection), MODE_ECO (Alg. 2/3), MODE_EXACT, MODE_MASTER.
  */
 int oracle_eco_step(const oracle_cfg *cfg, uint64_t numel, uint8_t *codes, REAL *scales, REAL *wreal,
                     const uint16_t *grad_bf16, const REAL *grad_real, REAL *m, REAL *v, const REAL *xi,
-                    REAL *dbg_theta, REAL *dbg_err) {
+                    REAL *aux, REAL *dbg_theta, REAL *dbg_err) {
   const int fmt = cfg->fmt, bs = cfg->block_size;
   const int quantized = (fmt == FMT_E4M3 || fmt == FMT_INT4);
   const int adam = (cfg->opt == OPT_ADAM);
-  const int inject = cfg->inject && fmt != FMT_BF16_PLAIN;
+  const int mode = (fmt == FMT_BF16_PLAIN) ? MODE_NAIVE : cfg->mode;
+  const int inject = (mode == MODE_ECO || mode == MODE_EXACT);
   grid_t G;
   double bc1, bc2;
-  REAL b1, omb1, b2, omb2, rbc2, c1, epsf, kap, wdf, lrf, alpha;
+  REAL b1, omb1, b2, omb2, rbc2, c1, epsf, kap, wdf, lrf, alpha, ca, cb;
   int64_t nb, b;
   int bad = 0;
 
@@ -351,6 +359,9 @@ int oracle_eco_step(const oracle_cfg *cfg, uint64_t numel, uint8_t *codes, REAL 
   if (fmt == FMT_INT4 && (bs & 1)) return -1;
   if (cfg->elem_offset % (uint64_t)bs) return -1;
   if (!m || (adam && !v) || (!grad_bf16 && !grad_real)) return -1;
+  if (mode < MODE_NAIVE || mode > MODE_MASTER) return -1;
+  if ((mode == MODE_EXACT || mode == MODE_MASTER) && !aux) return -1;
+  if (mode == MODE_EXACT && adam) return -1;                          /* Appendix A is stated for SGDM */
   if (quantized) make_grid(fmt, &G); else { G.n = 0; G.rho = 1.0; }
 
   /* scalars: formed in double, rounded once to REAL */
@@ -365,6 +376,8 @@ int oracle_eco_step(const oracle_cfg *cfg, uint64_t numel, uint8_t *codes, REAL 
   lrf = (REAL)cfg->lr;
   alpha = (REAL)((1.0 / cfg->lr) * (1.0 - 1.0 / cfg->beta1));        /* Eq. (alpha)            */
   wdf = (REAL)(cfg->lr * cfg->weight_decay);
+  ca = (REAL)(1.0 / cfg->lr);                                        /* Eq. (im_inject)        */
+  cb = (REAL)(1.0 / (cfg->lr * cfg->beta1));
 
   nb = (int64_t)((numel + (uint64_t)bs - 1) / (uint64_t)bs);
 #ifdef _OPENMP
@@ -385,7 +398,8 @@ int oracle_eco_step(const oracle_cfg *cfg, uint64_t numel, uint8_t *codes, REAL 
     for (j = 0; j < n; j++) {
       const uint64_t i = i0 + (uint64_t)j;
       REAL w, g, u;
-      if (quantized) w = decode(fmt, get_code(fmt, codes, i)) * scales[b];
+      if (mode == MODE_MASTER) w = aux[i];
+      else if (quantized) w = decode(fmt, get_code(fmt, codes, i)) * scales[b];
       else w = wreal[i];
       g = grad_bf16 ? bf16_bits_to_real(grad_bf16[i]) : grad_real[i];
       mt[j] = r_fma(b1, m[i], omb1 * g);
@@ -429,8 +443,10 @@ int oracle_eco_step(const oracle_cfg *cfg, uint64_t numel, uint8_t *codes, REAL 
       }
       e = th[j] - q;
       if (!quantized) wreal[i] = q;
-      if (inject) mh = adam ? r_fma(kap * dd[j], e, mt[j]) : r_fma(alpha, e, mt[j]);
+      if (mode == MODE_ECO) mh = adam ? r_fma(kap * dd[j], e, mt[j]) : r_fma(alpha, e, mt[j]);
+      else if (mode == MODE_EXACT) { mh = r_fma(-cb, e, r_fma(ca, aux[i], mt[j])); aux[i] = e; }
       else mh = mt[j];
+      if (mode == MODE_MASTER) aux[i] = th[j];
       m[i] = cfg->state_bf16 ? bf16_round_(mh) : mh;
       if (dbg_theta) dbg_theta[i] = th[j];
       if (dbg_err) dbg_err[i] = e;
