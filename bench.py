@@ -164,10 +164,7 @@ def main() -> int:
     if args.variant.endswith("rtn"):
         over["round"] = eco.ECO_ROUND_RTN
     t_setup = time.perf_counter()
-    dw = harness.DeviceWorkload(wl, "cuda:0")
-    if "opt" in over:
-        dw.plan.close()
-        dw.plan = eco.Plan([dw.descriptor(tv) for tv in dw.tensors], dw.hparams(1, **over))
+    dw = harness.DeviceWorkload(wl, "cuda:0", layout=over)
     torch.cuda.synchronize()
     print(f"[bench] {wl.name}: {len(wl.tensors)} tensors, {wl.numel} parameters, set-up {time.perf_counter() - t_setup:.1f} s",
           file=sys.stderr, flush=True)
@@ -177,7 +174,7 @@ def main() -> int:
     for _ in range(args.warmup):
         k += 1
         fill(k)
-        dw.step(k, **over)
+        dw.step(k)
     torch.cuda.synchronize()
 
     wall, kernel_ms = 0.0, []
@@ -188,7 +185,7 @@ def main() -> int:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record()
-        dw.step(k, **over)
+        dw.step(k)
         e1.record()
         torch.cuda.synchronize()
         wall += time.perf_counter() - t0

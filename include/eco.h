@@ -19,6 +19,7 @@
  *                                                         (Sec. 3.1, Eq. 1 and s = max|x|/rho)
  *     e  = theta~ - dec(code')*scale'                     (Alg. 3 line 2)
  *     m^ = m~ + ((1-b1^k)/lr)(1-1/b1) * d * e             (Alg. 3 line 5);  v^ = v~
+ * (ECO_MODE_ECO; see eco_mode_t for the naive, exact-injection and master-weight variants)
  * with `round` either round-to-nearest-even or stochastic rounding driven by a
  * counter-based Philox4x32-10 generator.  For SGD with momentum:
  *     m~ = b*m + (1-b)*g ; theta~ = theta^ - lr*m~ ; m^ = m~ + (1/lr)(1-1/b)*e
@@ -72,6 +73,16 @@ typedef enum { ECO_OPT_ADAM = 0, ECO_OPT_SGDM = 1 } eco_opt_t;       /* Alg. 3 /
 typedef enum { ECO_ROUND_SR = 0, ECO_ROUND_RTN = 1 } eco_round_t;    /* Sec. 3.1, rounding function  */
 typedef enum { ECO_DT_FP32 = 0, ECO_DT_BF16 = 1 } eco_dtype_t;
 
+/* What happens to the quantization error e = theta~ - q(theta~). */
+typedef enum {
+  ECO_MODE_NAIVE = 0,   /* nothing: master weights simply removed (Sec. 4.1 "FP8 w/o MW" baselines)               */
+  ECO_MODE_ECO = 1,     /* the paper's method: memory-free injection into m (Alg. 2 line 5 / Alg. 3 line 5)        */
+  ECO_MODE_EXACT = 2,   /* SGDM only: exact injection with a stored error, m <- m~ + e_t/eta - e_{t+1}/(eta beta)
+                           (Appendix A, Eq. im_inject); reproduces master-weight SGDM, costs 4 bytes/parameter     */
+  ECO_MODE_MASTER = 3   /* baseline WITH fp32 master weights (Sec. 3.1; Sec. 4.1 "FP8 w/ MW"): the update is applied
+                           to the master copy, weights = q(master), m is left alone                               */
+} eco_mode_t;
+
 /* One parameter tensor, flattened row-major.  Element i belongs to scale group i / block_size;
  * the last group may be shorter.  All pointers: device memory, 16-byte aligned. */
 typedef struct eco_tensor {
@@ -80,6 +91,8 @@ typedef struct eco_tensor {
   const void *grad;     /* numel bfloat16, read only                                                                       */
   void *m;              /* first moment, numel entries of state_dtype                                                      */
   void *v;              /* second moment, numel entries of state_dtype; ignored (may be NULL) for ECO_OPT_SGDM             */
+  void *aux;            /* numel fp32: ECO_MODE_EXACT: the stored error e_t (in: e_t, out: e_{t+1});
+                           ECO_MODE_MASTER: the master weights (in place); ignored (may be NULL) in the other modes        */
   uint64_t numel;       /* > 0                                                                                             */
   uint32_t tensor_id;   /* enters the random-number counter; keep it stable across steps and distinct across tensors      */
   int32_t fmt;          /* eco_format_t                                                                                    */
@@ -89,12 +102,12 @@ typedef struct eco_tensor {
 typedef struct eco_hparams {
   int32_t opt;            /* eco_opt_t                                                                     */
   int32_t round;          /* eco_round_t: rounding used when re-quantizing                                 */
-  int32_t inject;         /* 1: ECO (inject the error into m); 0: naive master-weight removal, m^ = m~     */
+  int32_t mode;           /* eco_mode_t; 1 = ECO                                                           */
   uint32_t block_size;    /* elements per scale group: 32, 64, 128, 256 or 512                             */
   int32_t state_dtype;    /* eco_dtype_t of m and v (math is fp32; bf16 state is rounded to nearest even)  */
   int32_t scale_dtype;    /* eco_dtype_t of the scales                                                     */
-  double lr;              /* eta  (> 0 when inject)                                                        */
-  double beta1;           /* beta1, or beta for SGDM (in (0,1) when inject: the injection divides by it)   */
+  double lr;              /* eta  (> 0 when the mode injects)                                              */
+  double beta1;           /* beta1, or beta for SGDM (in (0,1) when the mode injects: it divides by beta)  */
   double beta2;           /* beta2 (Adam only, in [0,1))                                                   */
   double eps;             /* epsilon (Adam only, >= 0)                                                     */
   double weight_decay;    /* decoupled decay lambda: theta^ <- theta^ - lr*lambda*theta^ before the update */
@@ -108,11 +121,12 @@ typedef struct eco_constants {
   float rbc2;                 /* 1/(1-beta2^k)                                       */
   float c1;                   /* lr/(1-beta1^k)  (Adam);                             */
   float eps;
-  float kappa;                /* ((1-beta1^k)/lr)(1-1/beta1)  (Alg. 3 line 5); 0 if !inject */
+  float kappa;                /* ((1-beta1^k)/lr)(1-1/beta1)  (Alg. 3 line 5); 0 unless ECO_MODE_ECO */
   float lr;                   /* eta (SGDM)                                          */
-  float alpha;                /* (1/lr)(1-1/beta)  (Eq. alpha); 0 if !inject         */
+  float alpha;                /* (1/lr)(1-1/beta)  (Eq. alpha); 0 unless ECO_MODE_ECO */
   float wd;                   /* lr*lambda                                           */
-  float reserved;
+  float inv_lr;               /* 1/lr          (Appendix A, Eq. im_inject); 0 unless ECO_MODE_EXACT */
+  float inv_lr_beta;          /* 1/(lr*beta)                                         */
 } eco_constants_t;
 
 typedef struct eco_plan eco_plan_t;
@@ -121,8 +135,8 @@ typedef struct eco_plan eco_plan_t;
  * eco_plan_create — validate a list of tensors and upload its launch tables (Alg. 1 is applied to
  * every tensor of the list by one eco_step call; tensors of different formats may be mixed).
  *   tensors, n : HOST array of n >= 1 descriptors (copied; may be freed after the call)
- *   layout     : HOST; only block_size, state_dtype, scale_dtype and opt are read (they fix the memory
- *                layout the descriptors are checked against)
+ *   layout     : HOST; only block_size, state_dtype, scale_dtype, opt and mode are read (they fix the
+ *                memory layout the descriptors are checked against)
  *   out        : receives the plan; owned by the library until eco_plan_destroy
  * Allocates device memory for the tables (about 64 bytes per tensor + 4 bytes per 512 elements) and
  * copies them synchronously.  Errors: ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_ENOMEM, ECO_EHIP.
@@ -135,7 +149,7 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan);
 /*
  * eco_step — one ECO step (Alg. 1 with Alg. 3 or Alg. 2) over every tensor of the plan.
  * Asynchronous on `stream`; allocates nothing; one kernel launch per storage format present.
- * hp->block_size, state_dtype, scale_dtype and opt must equal the plan's.
+ * hp->block_size, state_dtype, scale_dtype, opt and mode must equal the plan's.
  */
 eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream);
 

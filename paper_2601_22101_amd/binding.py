@@ -19,15 +19,17 @@ ECO_FMT_FP8_E4M3, ECO_FMT_INT4, ECO_FMT_BF16_PLAIN, ECO_FMT_FP32_IDENTITY = 0, 1
 ECO_OPT_ADAM, ECO_OPT_SGDM = 0, 1
 ECO_ROUND_SR, ECO_ROUND_RTN = 0, 1
 ECO_DT_FP32, ECO_DT_BF16 = 0, 1
+ECO_MODE_NAIVE, ECO_MODE_ECO, ECO_MODE_EXACT, ECO_MODE_MASTER = 0, 1, 2, 3
 
 
 class eco_tensor_t(C.Structure):
     _fields_ = [("weights", C.c_void_p), ("scales", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p),
-                ("v", C.c_void_p), ("numel", C.c_uint64), ("tensor_id", C.c_uint32), ("fmt", C.c_int32)]
+                ("v", C.c_void_p), ("aux", C.c_void_p), ("numel", C.c_uint64), ("tensor_id", C.c_uint32),
+                ("fmt", C.c_int32)]
 
 
 class eco_hparams_t(C.Structure):
-    _fields_ = [("opt", C.c_int32), ("round", C.c_int32), ("inject", C.c_int32), ("block_size", C.c_uint32),
+    _fields_ = [("opt", C.c_int32), ("round", C.c_int32), ("mode", C.c_int32), ("block_size", C.c_uint32),
                 ("state_dtype", C.c_int32), ("scale_dtype", C.c_int32),
                 ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
                 ("weight_decay", C.c_double), ("step", C.c_uint64), ("seed", C.c_uint64)]
@@ -35,7 +37,7 @@ class eco_hparams_t(C.Structure):
 
 class eco_constants_t(C.Structure):
     _fields_ = [(n, C.c_float) for n in ("b1", "omb1", "b2", "omb2", "rbc2", "c1", "eps", "kappa", "lr", "alpha",
-                                         "wd", "reserved")]
+                                         "wd", "inv_lr", "inv_lr_beta")]
 
 
 class EcoError(RuntimeError):
@@ -94,14 +96,17 @@ def _stream(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
-def make_tensor(weights, scales, grad, m, v, numel: int, tensor_id: int, fmt: int) -> eco_tensor_t:
-    return eco_tensor_t(_ptr(weights), _ptr(scales), _ptr(grad), _ptr(m), _ptr(v), numel, tensor_id, fmt)
+def make_tensor(weights, scales, grad, m, v, numel: int, tensor_id: int, fmt: int, aux=None) -> eco_tensor_t:
+    return eco_tensor_t(_ptr(weights), _ptr(scales), _ptr(grad), _ptr(m), _ptr(v), _ptr(aux), numel, tensor_id, fmt)
 
 
-def make_hparams(*, opt=ECO_OPT_ADAM, round=ECO_ROUND_SR, inject=True, block_size=128, state_dtype=ECO_DT_FP32,
-                 scale_dtype=ECO_DT_FP32, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, step=1,
-                 seed=0) -> eco_hparams_t:
-    return eco_hparams_t(opt, round, int(inject), block_size, state_dtype, scale_dtype, lr, beta1, beta2, eps,
+def make_hparams(*, opt=ECO_OPT_ADAM, round=ECO_ROUND_SR, inject=True, mode=None, block_size=128,
+                 state_dtype=ECO_DT_FP32, scale_dtype=ECO_DT_FP32, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
+                 weight_decay=0.0, step=1, seed=0) -> eco_hparams_t:
+    """`mode` is an ECO_MODE_* value; when omitted, `inject` chooses between ECO (True) and naive (False)."""
+    if mode is None:
+        mode = ECO_MODE_ECO if inject else ECO_MODE_NAIVE
+    return eco_hparams_t(opt, round, mode, block_size, state_dtype, scale_dtype, lr, beta1, beta2, eps,
                          weight_decay, step, seed & (2 ** 64 - 1))
 
 

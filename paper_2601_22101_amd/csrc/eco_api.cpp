@@ -56,14 +56,16 @@ eco_status_t check_hparams(const eco_hparams_t *hp) {
   if (!hp) return fail(ECO_EINVAL, "hyper-parameters: null pointer");
   if (hp->opt != ECO_OPT_ADAM && hp->opt != ECO_OPT_SGDM) return fail(ECO_EINVAL, "opt %d: unknown optimizer", hp->opt);
   if (hp->round != ECO_ROUND_SR && hp->round != ECO_ROUND_RTN) return fail(ECO_EINVAL, "round %d: unknown rounding", hp->round);
-  if (hp->inject != 0 && hp->inject != 1) return fail(ECO_EINVAL, "inject must be 0 or 1");
+  if (hp->mode < ECO_MODE_NAIVE || hp->mode > ECO_MODE_MASTER) return fail(ECO_EINVAL, "mode %d: unknown mode", hp->mode);
+  if (hp->mode == ECO_MODE_EXACT && hp->opt != ECO_OPT_SGDM)
+    return fail(ECO_EUNSUPPORTED, "exact stored-error injection is defined for SGDM only");
   if (!is_dtype(hp->state_dtype) || !is_dtype(hp->scale_dtype)) return fail(ECO_EINVAL, "unknown state or scale dtype");
   if (hp->step == 0) return fail(ECO_EINVAL, "step is 1-based: step == 0 has no bias correction");
   if (!std::isfinite(hp->lr) || hp->lr < 0.0) return fail(ECO_EINVAL, "lr must be finite and >= 0");
   if (!std::isfinite(hp->weight_decay) || hp->weight_decay < 0.0) return fail(ECO_EINVAL, "weight_decay must be finite and >= 0");
   if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0)) return fail(ECO_EINVAL, "beta1 must lie in [0, 1)");
-  if (hp->inject) {
-    // the injection strength divides by the learning rate and by beta (Eq. alpha; Alg. 3 line 5)
+  if (hp->mode == ECO_MODE_ECO || hp->mode == ECO_MODE_EXACT) {
+    // the injection strength divides by the learning rate and by beta (Eq. alpha; Alg. 3 line 5; Eq. im_inject)
     if (!(hp->lr > 0.0)) return fail(ECO_EINVAL, "error injection needs lr > 0");
     if (!(hp->beta1 > 0.0)) return fail(ECO_EINVAL, "error injection needs beta1 in (0, 1)");
   }
@@ -88,9 +90,13 @@ void derive_constants(const eco_hparams_t *hp, eco_constants_t *c) {
   c->eps = static_cast<float>(hp->eps);
   c->lr = static_cast<float>(hp->lr);
   c->wd = static_cast<float>(hp->lr * hp->weight_decay);
-  if (hp->inject) {
+  if (hp->mode == ECO_MODE_ECO) {
     c->kappa = static_cast<float>((bc1 / hp->lr) * (1.0 - 1.0 / hp->beta1));
     c->alpha = static_cast<float>((1.0 / hp->lr) * (1.0 - 1.0 / hp->beta1));
+  }
+  if (hp->mode == ECO_MODE_EXACT) {
+    c->inv_lr = static_cast<float>(1.0 / hp->lr);
+    c->inv_lr_beta = static_cast<float>(1.0 / (hp->lr * hp->beta1));
   }
 }
 
@@ -128,7 +134,7 @@ unsigned grid_for(uint64_t tiles, int cus) {
 struct eco_plan {
   uint32_t block_size = 0;
   int bs_shift = 0;
-  int32_t state_dtype = 0, scale_dtype = 0, opt = 0;
+  int32_t state_dtype = 0, scale_dtype = 0, opt = 0, mode = 0;
   int cus = 256;
   Group groups[4];   // indexed by eco_format_t
 };
@@ -197,6 +203,10 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   if (!layout) return fail(ECO_EINVAL, "plan: null layout");
   if (layout->opt != ECO_OPT_ADAM && layout->opt != ECO_OPT_SGDM) return fail(ECO_EINVAL, "opt %d: unknown optimizer", layout->opt);
   if (!is_dtype(layout->state_dtype) || !is_dtype(layout->scale_dtype)) return fail(ECO_EINVAL, "unknown state or scale dtype");
+  if (layout->mode < ECO_MODE_NAIVE || layout->mode > ECO_MODE_MASTER) return fail(ECO_EINVAL, "mode %d: unknown mode", layout->mode);
+  if (layout->mode == ECO_MODE_EXACT && layout->opt != ECO_OPT_SGDM)
+    return fail(ECO_EUNSUPPORTED, "exact stored-error injection is defined for SGDM only");
+  const bool needs_aux = layout->mode == ECO_MODE_EXACT || layout->mode == ECO_MODE_MASTER;
   int shift = 0;
   eco_status_t st = check_block_size(layout->block_size, &shift);
   if (st != ECO_OK) return st;
@@ -208,6 +218,7 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   plan->state_dtype = layout->state_dtype;
   plan->scale_dtype = layout->scale_dtype;
   plan->opt = layout->opt;
+  plan->mode = layout->mode;
 
   try {
     for (size_t i = 0; i < n; ++i) {
@@ -218,8 +229,9 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
       if (!t.weights || !t.grad || !t.m) { st = fail(ECO_EINVAL, "tensor %zu: null weights, grad or m", i); break; }
       if (quantized && !t.scales) { st = fail(ECO_EINVAL, "tensor %zu: quantized format needs scales", i); break; }
       if (layout->opt == ECO_OPT_ADAM && !t.v) { st = fail(ECO_EINVAL, "tensor %zu: Adam needs v", i); break; }
+      if (quantized && needs_aux && !t.aux) { st = fail(ECO_EINVAL, "tensor %zu: this mode needs the aux buffer", i); break; }
       if (!aligned16(t.weights) || !aligned16(t.grad) || !aligned16(t.m) || (quantized && !aligned16(t.scales)) ||
-          (layout->opt == ECO_OPT_ADAM && !aligned16(t.v))) {
+          (layout->opt == ECO_OPT_ADAM && !aligned16(t.v)) || (quantized && needs_aux && !aligned16(t.aux))) {
         st = fail(ECO_EALIGN, "tensor %zu: every data pointer must be 16-byte aligned", i);
         break;
       }
@@ -228,7 +240,7 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
       if (g.tile_tensor.size() + ntiles > 0xFFFFFFF0ull) { st = fail(ECO_EUNSUPPORTED, "plan: more than 2^32 tiles in one format"); break; }
       eco::TensorDesc d;
       std::memset(&d, 0, sizeof d);
-      d.w = t.weights; d.s = t.scales; d.g = t.grad; d.m = t.m; d.v = t.v;
+      d.w = t.weights; d.s = t.scales; d.g = t.grad; d.m = t.m; d.v = t.v; d.aux = t.aux;
       d.numel = t.numel;
       d.first_tile = static_cast<uint32_t>(g.tile_tensor.size());
       d.tensor_id = t.tensor_id;
@@ -266,8 +278,8 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
   eco_status_t st = check_hparams(hp);
   if (st != ECO_OK) return st;
   if (hp->block_size != plan->block_size || hp->state_dtype != plan->state_dtype || hp->scale_dtype != plan->scale_dtype ||
-      hp->opt != plan->opt)
-    return fail(ECO_EINVAL, "step: block_size, state_dtype, scale_dtype and opt must equal the plan's");
+      hp->opt != plan->opt || hp->mode != plan->mode)
+    return fail(ECO_EINVAL, "step: block_size, state_dtype, scale_dtype, opt and mode must equal the plan's");
 
   eco_constants_t c;
   derive_constants(hp, &c);
@@ -282,7 +294,7 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     a.num_ragged = static_cast<uint32_t>(g.ragged_tensor.size());
     a.bs_shift = static_cast<uint32_t>(plan->bs_shift);
     a.b1 = c.b1; a.omb1 = c.omb1; a.b2 = c.b2; a.omb2 = c.omb2; a.rbc2 = c.rbc2; a.c1 = c.c1; a.eps = c.eps;
-    a.kappa = c.kappa; a.lr = c.lr; a.alpha = c.alpha; a.wd = c.wd;
+    a.kappa = c.kappa; a.lr = c.lr; a.alpha = c.alpha; a.wd = c.wd; a.inv_lr = c.inv_lr; a.inv_lr_beta = c.inv_lr_beta;
     a.seed_lo = static_cast<uint32_t>(hp->seed);
     a.seed_hi = static_cast<uint32_t>(hp->seed >> 32);
     a.step_lo = static_cast<uint32_t>(hp->step);
@@ -294,7 +306,9 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     kv.fmt = f;
     kv.state_bf16 = hp->state_dtype == ECO_DT_BF16;
     kv.scale_bf16 = hp->scale_dtype == ECO_DT_BF16;
-    kv.opt = hp->opt;
+    if (hp->mode == ECO_MODE_MASTER) kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM_MASTER : eco::ALGO_SGDM_MASTER;
+    else if (hp->mode == ECO_MODE_EXACT) kv.algo = eco::ALGO_SGDM_EXACT;
+    else kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM : eco::ALGO_SGDM;
     kv.round = hp->round;
     const hipError_t e = eco::launch_step(kv, a, grid_for(a.num_tiles, plan->cus), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "step kernel launch");

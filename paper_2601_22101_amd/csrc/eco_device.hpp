@@ -6,11 +6,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "eco_internal.hpp"
+
 namespace eco {
 
-enum : int { FMT_FP8 = 0, FMT_INT4 = 1, FMT_BF16_PLAIN = 2, FMT_FP32_ID = 3 };
-enum : int { OPT_ADAM = 0, OPT_SGDM = 1 };
-enum : int { ROUND_SR = 0, ROUND_RTN = 1 };
 
 __device__ __forceinline__ uint32_t f2u(float x) { return __float_as_uint(x); }
 __device__ __forceinline__ float u2f(uint32_t x) { return __uint_as_float(x); }

@@ -5,6 +5,15 @@
 
 namespace eco {
 
+enum : int { FMT_FP8 = 0, FMT_INT4 = 1, FMT_BF16_PLAIN = 2, FMT_FP32_ID = 3 };
+enum : int { ROUND_SR = 0, ROUND_RTN = 1 };
+// optimizer x treatment of the quantization error: Adam / SGDM with the memory-free injection (or none,
+// when the injection constants are zero), SGDM with the exact stored-error injection, and the
+// master-weight baselines
+enum : int { ALGO_ADAM = 0, ALGO_SGDM = 1, ALGO_SGDM_EXACT = 2, ALGO_ADAM_MASTER = 3, ALGO_SGDM_MASTER = 4 };
+constexpr bool algo_is_adam(int a) { return a == ALGO_ADAM || a == ALGO_ADAM_MASTER; }
+constexpr bool algo_is_master(int a) { return a == ALGO_ADAM_MASTER || a == ALGO_SGDM_MASTER; }
+
 // A tile is TILE_ELEMS consecutive elements of one tensor, processed by one workgroup of one wave,
 // 8 consecutive elements per lane.  A scale group of B elements therefore occupies B/8 consecutive
 // lanes (B = 32..512 fits inside the 64-lane wave).
@@ -28,10 +37,10 @@ struct TensorDesc {          // 64 bytes, device table entry
   const void *g;             // bf16 gradient
   void *m;
   void *v;
+  void *aux;                 // fp32: stored error (exact injection) or master weights
   uint64_t numel;
   uint32_t first_tile;       // index of this tensor's first full tile in the group's tile list
   uint32_t tensor_id;
-  uint64_t pad;
 };
 static_assert(sizeof(TensorDesc) == 64, "TensorDesc layout");
 
@@ -42,7 +51,7 @@ struct StepArgs {            // by-value kernel argument: everything wave-unifor
   uint32_t num_tiles;            // full tiles
   uint32_t num_ragged;
   uint32_t bs_shift;             // log2(block_size)
-  float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd;
+  float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd, inv_lr, inv_lr_beta;
   uint32_t seed_lo, seed_hi, step_lo;
   uint32_t lds_bytes;            // host side only: dynamic LDS per workgroup of the step kernel
 };
@@ -51,7 +60,7 @@ struct KernelVariant {
   int fmt;          // FMT_*
   int state_bf16;   // m, v stored as bfloat16
   int scale_bf16;
-  int opt;          // OPT_*
+  int algo;         // ALGO_*
   int round;        // ROUND_*
 };
 

@@ -10,7 +10,7 @@ namespace eco {
 // nearest even, no injection (the method is applied to linear layers only; norm weights take the
 // ordinary optimizer).  FMT_FP32_ID: fp32 weights under the identity quantizer, for which the
 // quantization error is zero and Alg. 2/3 add nothing to the momentum.
-template <int FMT, bool STATE_BF16, int OPT, bool FULL>
+template <int FMT, bool STATE_BF16, bool ADAM, bool FULL>
 __device__ __forceinline__ void plain_tile(const StepArgs &a, const TensorDesc &td, uint64_t e0) {
   int nvalid = 8;
   if (!FULL) {
@@ -21,13 +21,13 @@ __device__ __forceinline__ void plain_tile(const StepArgs &a, const TensorDesc &
   load_state8<FMT == FMT_BF16_PLAIN, FULL>(td.w, e0, nvalid, w);
   load_bf16x8<FULL>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
   load_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
-  if (OPT == OPT_ADAM) load_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
+  if (ADAM) load_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     float wj = w[j];
     m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
     float u;
-    if (OPT == OPT_ADAM) {
+    if (ADAM) {
       v[j] = fmaf(a.b2, v[j], a.omb2 * (g[j] * g[j]));
       const float d = sqrtf(v[j] * a.rbc2) + a.eps;
       u = (a.c1 * m[j]) / d;
@@ -39,24 +39,24 @@ __device__ __forceinline__ void plain_tile(const StepArgs &a, const TensorDesc &
   }
   store_state8<FMT == FMT_BF16_PLAIN, FULL>(td.w, e0, nvalid, w);
   store_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
-  if (OPT == OPT_ADAM) store_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
+  if (ADAM) store_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
 }
 
-template <int FMT, bool STATE_BF16, int OPT>
+template <int FMT, bool STATE_BF16, bool ADAM>
 __global__ __launch_bounds__(WG_THREADS) void eco_plain_kernel(const StepArgs a) {
   for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
     const TensorDesc td = load_tensor_desc(a, load_tile_tensor(a, tile));
     const uint64_t tile_off = (uint64_t)(tile - td.first_tile) * TILE_ELEMS;
-    plain_tile<FMT, STATE_BF16, OPT, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+    plain_tile<FMT, STATE_BF16, ADAM, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
   }
 }
 
-template <int FMT, bool STATE_BF16, int OPT>
+template <int FMT, bool STATE_BF16, bool ADAM>
 __global__ __launch_bounds__(WG_THREADS) void eco_plain_ragged_kernel(const StepArgs a) {
   const ECO_CONST_AS uint32_t *rt = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.ragged_tensor;
   const TensorDesc td = load_tensor_desc(a, rt[blockIdx.x]);
   const uint64_t tile_off = td.numel / TILE_ELEMS * TILE_ELEMS;
-  plain_tile<FMT, STATE_BF16, OPT, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+  plain_tile<FMT, STATE_BF16, ADAM, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
 }
 
 hipError_t launch_step_plain(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
@@ -68,16 +68,16 @@ hipError_t launch_step_plain(const KernelVariant &kv, const StepArgs &args, unsi
       hipLaunchKernelGGL((eco_plain_ragged_kernel<F, ST, OP>), dim3(args.num_ragged), dim3(WG_THREADS), 0,     \
                          stream, args);                                                                        \
   } while (0)
-  const int key = (kv.fmt == FMT_FP32_ID ? 4 : 0) | (kv.state_bf16 ? 2 : 0) | (kv.opt == OPT_SGDM ? 1 : 0);
+  const int key = (kv.fmt == FMT_FP32_ID ? 4 : 0) | (kv.state_bf16 ? 2 : 0) | (algo_is_adam(kv.algo) ? 0 : 1);
   switch (key) {
-    case 0: ECO_LAUNCH(FMT_BF16_PLAIN, false, OPT_ADAM); break;
-    case 1: ECO_LAUNCH(FMT_BF16_PLAIN, false, OPT_SGDM); break;
-    case 2: ECO_LAUNCH(FMT_BF16_PLAIN, true, OPT_ADAM); break;
-    case 3: ECO_LAUNCH(FMT_BF16_PLAIN, true, OPT_SGDM); break;
-    case 4: ECO_LAUNCH(FMT_FP32_ID, false, OPT_ADAM); break;
-    case 5: ECO_LAUNCH(FMT_FP32_ID, false, OPT_SGDM); break;
-    case 6: ECO_LAUNCH(FMT_FP32_ID, true, OPT_ADAM); break;
-    default: ECO_LAUNCH(FMT_FP32_ID, true, OPT_SGDM); break;
+    case 0: ECO_LAUNCH(FMT_BF16_PLAIN, false, true); break;
+    case 1: ECO_LAUNCH(FMT_BF16_PLAIN, false, false); break;
+    case 2: ECO_LAUNCH(FMT_BF16_PLAIN, true, true); break;
+    case 3: ECO_LAUNCH(FMT_BF16_PLAIN, true, false); break;
+    case 4: ECO_LAUNCH(FMT_FP32_ID, false, true); break;
+    case 5: ECO_LAUNCH(FMT_FP32_ID, false, false); break;
+    case 6: ECO_LAUNCH(FMT_FP32_ID, true, true); break;
+    default: ECO_LAUNCH(FMT_FP32_ID, true, false); break;
   }
 #undef ECO_LAUNCH
   return hipGetLastError();

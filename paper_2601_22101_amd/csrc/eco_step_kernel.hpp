@@ -18,6 +18,9 @@
 //       [bf16 scales: s' = bf16(a/rho), inv = 1/s'];  if inv is not finite: s' = inv = 0
 //   y = theta~ * inv;  code' = round(y);  q = dec(code') * s';  e = theta~ - q
 //   m^ = fma(kappa*d, e, m~)          [SGDM: fma(alpha, e, m~)]
+// Variants (template parameter ALGO):
+//   exact injection (Appendix A, SGDM):  m^ = fma(-inv_lr_beta, e, fma(inv_lr, e_old, m~)), e stored for the next step
+//   master weights (Sec. 3.1):           w is read from / theta~ written to an fp32 master copy, m^ = m~
 #pragma once
 #include "eco_device.hpp"
 #include "eco_internal.hpp"
@@ -208,8 +211,10 @@ __device__ __forceinline__ void sqrt_plus_eps8(const float (&x)[8], float eps, f
   }
 }
 
-template <int FMT, bool STATE_BF16, bool SCALE_BF16, int OPT, int ROUND, bool FULL>
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, bool FULL>
 __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &td, uint64_t e0) {
+  constexpr bool ADAM = algo_is_adam(ALGO);
+  constexpr bool MASTER = algo_is_master(ALGO);
   int nvalid = 8;
   if (!FULL) {
     const int64_t left = (int64_t)td.numel - (int64_t)e0;
@@ -217,22 +222,25 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
   }
   const uint64_t blk = e0 >> a.bs_shift;
 
-  uint32_t c[2];
-  float g[8], m[8], v[8];
-  load_codes8<FMT, FULL>(td.w, e0, nvalid, c);
+  float g[8], m[8], v[8], w[8];
   load_bf16x8<FULL>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
   load_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
-  if (OPT == OPT_ADAM) load_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
-  const float s_old = (FULL || nvalid > 0) ? load_scale<SCALE_BF16>(td.s, blk) : 0.0f;
+  if (ADAM) load_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
+  if (MASTER) {
+    load_f32x8<FULL>(static_cast<const float *>(td.aux) + e0, nvalid, w);
+  } else {
+    uint32_t c[2];
+    load_codes8<FMT, FULL>(td.w, e0, nvalid, c);
+    const float s_old = (FULL || nvalid > 0) ? load_scale<SCALE_BF16>(td.s, blk) : 0.0f;
+    w[0] = decode_elem<FMT, 0>(c) * s_old; w[1] = decode_elem<FMT, 1>(c) * s_old;
+    w[2] = decode_elem<FMT, 2>(c) * s_old; w[3] = decode_elem<FMT, 3>(c) * s_old;
+    w[4] = decode_elem<FMT, 4>(c) * s_old; w[5] = decode_elem<FMT, 5>(c) * s_old;
+    w[6] = decode_elem<FMT, 6>(c) * s_old; w[7] = decode_elem<FMT, 7>(c) * s_old;
+  }
 
-  float w[8];
-  w[0] = decode_elem<FMT, 0>(c); w[1] = decode_elem<FMT, 1>(c); w[2] = decode_elem<FMT, 2>(c);
-  w[3] = decode_elem<FMT, 3>(c); w[4] = decode_elem<FMT, 4>(c); w[5] = decode_elem<FMT, 5>(c);
-  w[6] = decode_elem<FMT, 6>(c); w[7] = decode_elem<FMT, 7>(c);
-
-  // OPTIM_STEP on the de-quantized weights
+  // OPTIM_STEP on the de-quantized (or master) weights
   float th[8], d[8];
-  if (OPT == OPT_ADAM) {
+  if (ADAM) {
     float x[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -245,9 +253,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
   }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    float wj = w[j] * s_old;
+    float wj = w[j];
     float u;
-    if (OPT == OPT_ADAM) {
+    if (ADAM) {
       u = (a.c1 * m[j]) / d[j];
     } else {
       m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
@@ -258,6 +266,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
     th[j] = wj - u;
     if (!FULL && j >= nvalid) th[j] = 0.0f;
   }
+  if (MASTER) store_f32x8<FULL>(static_cast<float *>(td.aux) + e0, nvalid, th);
 
   // ECO_QUANTIZE
   const float amax = u2f(group_umax(f2u(absmax8(th)), 1 << (a.bs_shift - 3)));
@@ -280,15 +289,20 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
   }
   store_codes8<FMT, FULL>(td.w, e0, nvalid, cn);
 
-  float qn[8];
-  qn[0] = decode_elem<FMT, 0>(cn); qn[1] = decode_elem<FMT, 1>(cn); qn[2] = decode_elem<FMT, 2>(cn);
-  qn[3] = decode_elem<FMT, 3>(cn); qn[4] = decode_elem<FMT, 4>(cn); qn[5] = decode_elem<FMT, 5>(cn);
-  qn[6] = decode_elem<FMT, 6>(cn); qn[7] = decode_elem<FMT, 7>(cn);
+  if (!MASTER) {
+    float qn[8], eo[8];
+    qn[0] = decode_elem<FMT, 0>(cn); qn[1] = decode_elem<FMT, 1>(cn); qn[2] = decode_elem<FMT, 2>(cn);
+    qn[3] = decode_elem<FMT, 3>(cn); qn[4] = decode_elem<FMT, 4>(cn); qn[5] = decode_elem<FMT, 5>(cn);
+    qn[6] = decode_elem<FMT, 6>(cn); qn[7] = decode_elem<FMT, 7>(cn);
+    if (ALGO == ALGO_SGDM_EXACT) load_f32x8<FULL>(static_cast<const float *>(td.aux) + e0, nvalid, eo);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float e = th[j] - qn[j] * s_new;
-    if (OPT == OPT_ADAM) m[j] = fmaf(a.kappa * d[j], e, m[j]);
-    else m[j] = fmaf(a.alpha, e, m[j]);
+    for (int j = 0; j < 8; ++j) {
+      const float e = th[j] - qn[j] * s_new;
+      if (ALGO == ALGO_ADAM) m[j] = fmaf(a.kappa * d[j], e, m[j]);
+      else if (ALGO == ALGO_SGDM) m[j] = fmaf(a.alpha, e, m[j]);
+      else { m[j] = fmaf(-a.inv_lr_beta, e, fmaf(a.inv_lr, eo[j], m[j])); eo[j] = e; }
+    }
+    if (ALGO == ALGO_SGDM_EXACT) store_f32x8<FULL>(static_cast<float *>(td.aux) + e0, nvalid, eo);
   }
   store_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
 
@@ -318,59 +332,66 @@ __device__ __forceinline__ TensorDesc load_tensor_desc(const StepArgs &a, uint32
   td.g = (const void *)(uintptr_t)p[2];
   td.m = (void *)(uintptr_t)p[3];
   td.v = (void *)(uintptr_t)p[4];
-  td.numel = p[5];
-  const uint64_t ft = p[6];
+  td.aux = (void *)(uintptr_t)p[5];
+  td.numel = p[6];
+  const uint64_t ft = p[7];
   td.first_tile = (uint32_t)ft;
   td.tensor_id = (uint32_t)(ft >> 32);
-  td.pad = 0;
   return td;
 }
 
 // Persistent kernel over the full tiles: workgroup b handles tiles b, b + gridDim.x, ...  The
 // tile -> tensor table and the tensor descriptors are wave-uniform and are fetched with scalar loads.
-template <int FMT, bool STATE_BF16, bool SCALE_BF16, int OPT, int ROUND>
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(WG_THREADS, 8) void eco_step_kernel(const StepArgs a) {
   for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
     const TensorDesc td = load_tensor_desc(a, load_tile_tensor(a, tile));
     const uint64_t tile_off = (uint64_t)(tile - td.first_tile) * TILE_ELEMS;
-    step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+    step_tile<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
   }
 }
 
 // The last, partial tile of each tensor whose length is not a multiple of TILE_ELEMS: one workgroup
 // per such tensor, element-wise guarded accesses.  A separate kernel keeps the guards' registers and
 // branches out of the full-tile kernel.
-template <int FMT, bool STATE_BF16, bool SCALE_BF16, int OPT, int ROUND>
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(WG_THREADS) void eco_step_ragged_kernel(const StepArgs a) {
   const ECO_CONST_AS uint32_t *rt = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.ragged_tensor;
   const TensorDesc td = load_tensor_desc(a, rt[blockIdx.x]);
   const uint64_t tile_off = td.numel / TILE_ELEMS * TILE_ELEMS;
-  step_tile<FMT, STATE_BF16, SCALE_BF16, OPT, ROUND, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+  step_tile<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+}
+
+template <int FMT, bool STATE_BF16, bool SC, int RD>
+void launch_step_algos(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
+#define ECO_LAUNCH(AL)                                                                                      \
+  do {                                                                                                      \
+    if (args.num_tiles)                                                                                     \
+      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(grid), dim3(WG_THREADS),      \
+                         args.lds_bytes, stream, args);                                                     \
+    if (args.num_ragged)                                                                                    \
+      hipLaunchKernelGGL((eco_step_ragged_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_ragged),      \
+                         dim3(WG_THREADS), 0, stream, args);                                                \
+  } while (0)
+  switch (kv.algo) {
+    case ALGO_ADAM: ECO_LAUNCH(ALGO_ADAM); break;
+    case ALGO_SGDM: ECO_LAUNCH(ALGO_SGDM); break;
+    case ALGO_SGDM_EXACT: ECO_LAUNCH(ALGO_SGDM_EXACT); break;
+    case ALGO_ADAM_MASTER: ECO_LAUNCH(ALGO_ADAM_MASTER); break;
+    default: ECO_LAUNCH(ALGO_SGDM_MASTER); break;
+  }
+#undef ECO_LAUNCH
 }
 
 template <int FMT, bool STATE_BF16>
 hipError_t launch_step_variants(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(SC, OP, RD)                                                                              \
-  do {                                                                                                      \
-    if (args.num_tiles)                                                                                     \
-      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(grid), dim3(WG_THREADS),      \
-                         args.lds_bytes, stream, args);                                                     \
-    if (args.num_ragged)                                                                                    \
-      hipLaunchKernelGGL((eco_step_ragged_kernel<FMT, STATE_BF16, SC, OP, RD>), dim3(args.num_ragged),      \
-                         dim3(WG_THREADS), 0, stream, args);                                                \
-  } while (0)
-  const int key = (kv.scale_bf16 ? 4 : 0) | (kv.opt == OPT_SGDM ? 2 : 0) | (kv.round == ROUND_RTN ? 1 : 0);
+  const int key = (kv.scale_bf16 ? 2 : 0) | (kv.round == ROUND_RTN ? 1 : 0);
   switch (key) {
-    case 0: ECO_LAUNCH(false, OPT_ADAM, ROUND_SR); break;
-    case 1: ECO_LAUNCH(false, OPT_ADAM, ROUND_RTN); break;
-    case 2: ECO_LAUNCH(false, OPT_SGDM, ROUND_SR); break;
-    case 3: ECO_LAUNCH(false, OPT_SGDM, ROUND_RTN); break;
-    case 4: ECO_LAUNCH(true, OPT_ADAM, ROUND_SR); break;
-    case 5: ECO_LAUNCH(true, OPT_ADAM, ROUND_RTN); break;
-    case 6: ECO_LAUNCH(true, OPT_SGDM, ROUND_SR); break;
-    default: ECO_LAUNCH(true, OPT_SGDM, ROUND_RTN); break;
+    case 0: launch_step_algos<FMT, STATE_BF16, false, ROUND_SR>(kv, args, grid, stream); break;
+    case 1: launch_step_algos<FMT, STATE_BF16, false, ROUND_RTN>(kv, args, grid, stream); break;
+    case 2: launch_step_algos<FMT, STATE_BF16, true, ROUND_SR>(kv, args, grid, stream); break;
+    default: launch_step_algos<FMT, STATE_BF16, true, ROUND_RTN>(kv, args, grid, stream); break;
   }
-#undef ECO_LAUNCH
   return hipGetLastError();
 }
 

@@ -33,6 +33,7 @@ class TensorViews:
     grad: torch.Tensor             # bf16
     m: torch.Tensor
     v: torch.Tensor
+    aux: Optional[torch.Tensor] = None   # fp32 master weights or stored error, when the mode uses one
 
 
 class DeviceWorkload:
@@ -41,8 +42,13 @@ class DeviceWorkload:
     has its own descriptor in the plan and its own, 256-byte aligned, slices."""
 
     def __init__(self, wl: Workload, device: str = "cuda:0", base_seed: int = workloads.BASE_SEED,
-                 init: bool = True):
+                 init: bool = True, layout: Optional[dict] = None):
+        """`layout`: hyper-parameter overrides that are fixed for the life of the plan (opt, mode, ...).
+        In the master-weight mode the fp32 initial weights are kept as the master copy; in the
+        exact-injection mode the aux buffer starts as e_0 = theta_0 - q(theta_0) (Appendix A)."""
         self.wl = wl
+        self.layout = dict(layout or {})
+        self.mode = self.layout.get("mode", eco.ECO_MODE_ECO if self.layout.get("inject", True) else eco.ECO_MODE_NAIVE)
         self.device = torch.device(device)
         self.base_seed = base_seed
         self.state_dtype = torch.bfloat16 if wl.state_bf16 else torch.float32
@@ -78,6 +84,8 @@ class DeviceWorkload:
         self.grad = torch.zeros(off, dtype=torch.bfloat16, device=dev)
         self.m = torch.zeros(off, dtype=self.state_dtype, device=dev)
         self.v = torch.zeros(off, dtype=self.state_dtype, device=dev)
+        self.aux = (torch.zeros(off, dtype=torch.float32, device=dev)
+                    if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER) else None)
 
         self.tensors: List[TensorViews] = []
         for i, t in enumerate(wl.tensors):
@@ -91,7 +99,7 @@ class DeviceWorkload:
                 s = None
             o = offs[i]
             self.tensors.append(TensorViews(t, i, _FMT[t.fmt], w, s, self.grad[o:o + n], self.m[o:o + n],
-                                            self.v[o:o + n]))
+                                            self.v[o:o + n], None if self.aux is None else self.aux[o:o + n]))
         if init:
             self.init_weights()
         self.plan = eco.Plan([self.descriptor(tv) for tv in self.tensors], self.hparams(1))
@@ -102,7 +110,8 @@ class DeviceWorkload:
         return self.wl.numel
 
     def descriptor(self, tv: TensorViews) -> "eco.eco_tensor_t":
-        return eco.make_tensor(tv.weights, tv.scales, tv.grad, tv.m, tv.v, tv.spec.numel, tv.tensor_id, tv.fmt)
+        return eco.make_tensor(tv.weights, tv.scales, tv.grad, tv.m, tv.v, tv.spec.numel, tv.tensor_id, tv.fmt,
+                               aux=tv.aux)
 
     def hparams(self, step: int, **over) -> "eco.eco_hparams_t":
         wl = self.wl
@@ -110,6 +119,7 @@ class DeviceWorkload:
                   state_dtype=eco.ECO_DT_BF16 if wl.state_bf16 else eco.ECO_DT_FP32,
                   scale_dtype=eco.ECO_DT_BF16 if wl.scale_bf16 else eco.ECO_DT_FP32,
                   lr=wl.lr_at(step), beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, step=step, seed=self.base_seed)
+        kw.update(self.layout)
         kw.update(over)
         return eco.make_hparams(**kw)
 
@@ -119,8 +129,14 @@ class DeviceWorkload:
         for tv in self.tensors:
             w = workloads.initial_weights(wl, tv.tensor_id, device=self.device, base_seed=self.base_seed)
             if tv.fmt in (eco.ECO_FMT_FP8_E4M3, eco.ECO_FMT_INT4):
-                eco.eco_quantize_init(w, eco.ECO_DT_FP32, tv.spec.numel, tv.fmt, wl.block_size,
-                                      eco.ECO_DT_BF16 if wl.scale_bf16 else eco.ECO_DT_FP32, tv.weights, tv.scales)
+                sdt = eco.ECO_DT_BF16 if wl.scale_bf16 else eco.ECO_DT_FP32
+                eco.eco_quantize_init(w, eco.ECO_DT_FP32, tv.spec.numel, tv.fmt, wl.block_size, sdt, tv.weights,
+                                      tv.scales)
+                if self.mode == eco.ECO_MODE_MASTER:
+                    tv.aux.copy_(w)
+                elif self.mode == eco.ECO_MODE_EXACT:
+                    eco.eco_dequantize(tv.weights, tv.scales, tv.spec.numel, tv.fmt, wl.block_size, sdt, tv.aux)
+                    torch.sub(w, tv.aux, out=tv.aux)            # e_0 = theta_0 - q(theta_0)
             else:
                 tv.weights.copy_(w.to(torch.bfloat16))
             del w

@@ -35,6 +35,8 @@ def to_f32(t: torch.Tensor) -> np.ndarray:
 def host_copy(tv) -> dict:
     """Host copies of one tensor's arrays (a TensorViews of the harness, or anything shaped like it)."""
     d = dict(grad=bf16_bits(tv.grad), m=to_f32(tv.m), v=to_f32(tv.v) if tv.v is not None else None)
+    if getattr(tv, "aux", None) is not None:
+        d["aux"] = to_f32(tv.aux)
     if tv.scales is not None:
         d["codes"] = tv.weights.detach().cpu().numpy().copy()
         d["scales"] = to_f32(tv.scales)
@@ -44,8 +46,9 @@ def host_copy(tv) -> dict:
 
 
 def oracle_step(o, h: dict, numel: int, cfg: StepConfig) -> None:
+    aux = h.get("aux") if cfg.mode in (oracle.MODE_EXACT, oracle.MODE_MASTER) and "codes" in h else None
     rc = o.eco_step(cfg, numel, h["m"], h.get("v"), codes=h.get("codes"), scales=h.get("scales"),
-                    wreal=h.get("wreal"), grad_bf16=h["grad"])
+                    wreal=h.get("wreal"), grad_bf16=h["grad"], aux=aux)
     assert rc == 0, rc
 
 
@@ -64,6 +67,11 @@ def compare(gpu: dict, ref: dict, what: str = "", state_bf16: bool = False) -> d
         wg, wr = gpu["wreal"], ref["wreal"]
         stats["weight_mismatch"] = int((wg.view(np.uint32) != wr.view(np.uint32)).sum())
         assert stats["weight_mismatch"] <= MAX_FLIP_RATE * n, f"{what}: {stats['weight_mismatch']} weights differ"
+    if "aux" in ref and "aux" in gpu and "codes" in ref:
+        stats["aux_bit_mismatch"] = int((gpu["aux"].view(np.uint32) != ref["aux"].view(np.uint32)).sum())
+        ok = np.ones(n, bool) if not stats.get("code_mismatch") else ~_elements_of(diff, n)
+        a, b = gpu["aux"].astype(np.float64), ref["aux"].astype(np.float64)
+        assert np.all(np.abs(a - b)[ok] <= STATE_RTOL * np.maximum(np.abs(b)[ok], 1e-30)), f"{what}: aux differs"
     for key in ("m", "v"):
         if ref.get(key) is None:
             continue
@@ -94,7 +102,7 @@ def _elements_of(byte_diff: np.ndarray, n: int) -> np.ndarray:
 
 def step_config(hp, tensor_id: int, fmt: int, elem_offset: int = 0) -> StepConfig:
     """The oracle's view of the library's hyper-parameter struct."""
-    return StepConfig(fmt=ORACLE_FMT[fmt], opt=hp.opt, round=hp.round, inject=bool(hp.inject),
+    return StepConfig(fmt=ORACLE_FMT[fmt], opt=hp.opt, round=hp.round, mode=hp.mode,
                       block_size=hp.block_size, state_bf16=bool(hp.state_dtype), scale_bf16=bool(hp.scale_dtype),
                       lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, weight_decay=hp.weight_decay,
                       step=hp.step, seed=hp.seed, elem_offset=elem_offset, tensor_id=tensor_id)

@@ -36,14 +36,14 @@ def test_every_declared_symbol_is_exported(eco):
 
 
 def test_struct_layouts_match_header(eco):
-    assert C.sizeof(eco.eco_tensor_t) == 56
+    assert C.sizeof(eco.eco_tensor_t) == 64
     assert C.sizeof(eco.eco_hparams_t) == 80
-    assert C.sizeof(eco.eco_constants_t) == 48
+    assert C.sizeof(eco.eco_constants_t) == 52
 
 
 def _tensor(eco, **kw):
     base = dict(weights=0x1000, scales=0x2000, grad=0x3000, m=0x4000, v=0x5000, numel=4096, tensor_id=0,
-                fmt=eco.ECO_FMT_FP8_E4M3)
+                fmt=eco.ECO_FMT_FP8_E4M3, aux=None)
     base.update(kw)
     return eco.make_tensor(**base)
 
@@ -78,6 +78,13 @@ def test_plan_validation_happens_before_any_device_work(eco):
                      (1024, eco.ECO_EUNSUPPORTED)):
         assert _status(eco, eco.eco_plan_create, [_tensor(eco)], eco.make_hparams(block_size=bs)) == want
     assert _status(eco, eco.eco_plan_create, [_tensor(eco)], eco.make_hparams(state_dtype=5)) == eco.ECO_EINVAL
+    # the master-weight and exact-injection modes need the aux buffer, aligned
+    for mode, opt in ((eco.ECO_MODE_MASTER, eco.ECO_OPT_ADAM), (eco.ECO_MODE_EXACT, eco.ECO_OPT_SGDM)):
+        hp2 = eco.make_hparams(mode=mode, opt=opt)
+        assert _status(eco, eco.eco_plan_create, [_tensor(eco)], hp2) == eco.ECO_EINVAL
+        assert _status(eco, eco.eco_plan_create, [_tensor(eco, aux=0x6004)], hp2) == eco.ECO_EALIGN
+    assert _status(eco, eco.eco_plan_create, [_tensor(eco, aux=0x6000)],
+                   eco.make_hparams(mode=eco.ECO_MODE_EXACT)) == eco.ECO_EUNSUPPORTED
     # SGDM does not need v
     st = _status(eco, eco.eco_plan_create, [_tensor(eco, v=None)], eco.make_hparams(opt=eco.ECO_OPT_SGDM))
     assert st in (eco.ECO_OK, eco.ECO_EHIP, eco.ECO_ENOMEM)      # passes validation; no GPU here -> HIP error
@@ -88,7 +95,7 @@ def test_hparams_validation(eco):
     eco.eco_step_constants(eco.make_hparams(**ok))
     for kw in (dict(step=0), dict(lr=0.0), dict(lr=-1.0), dict(lr=float("nan")), dict(beta1=0.0), dict(beta1=1.0),
                dict(beta2=1.0), dict(beta2=-0.1), dict(eps=-1.0), dict(weight_decay=-0.1), dict(opt=3),
-               dict(round=2), dict(inject=2), dict(state_dtype=9)):
+               dict(round=2), dict(mode=4), dict(mode=-1), dict(state_dtype=9)):
         assert _status(eco, eco.eco_step_constants, eco.make_hparams(**{**ok, **kw})) == eco.ECO_EINVAL, kw
     # without injection nothing divides by lr or beta1
     eco.eco_step_constants(eco.make_hparams(**{**ok, "lr": 0.0, "inject": False}))
@@ -130,7 +137,14 @@ def test_step_constants_follow_the_paper(eco):
             assert abs(got - want) <= abs(want) * 2.0 ** -23
         assert c.kappa < 0 and c.alpha < 0
     c = eco.eco_step_constants(eco.make_hparams(inject=False))
+    assert c.kappa == 0 and c.alpha == 0 and c.inv_lr == 0
+    # exact stored-error injection (Appendix A): 1/eta and 1/(eta beta); SGDM only
+    c = eco.eco_step_constants(eco.make_hparams(opt=eco.ECO_OPT_SGDM, mode=eco.ECO_MODE_EXACT, lr=0.05, beta1=0.9))
     assert c.kappa == 0 and c.alpha == 0
+    assert abs(c.inv_lr - 20.0) < 1e-5 and abs(c.inv_lr_beta - 1 / 0.045) < 1e-5
+    assert _status(eco, eco.eco_step_constants, eco.make_hparams(mode=eco.ECO_MODE_EXACT)) == eco.ECO_EUNSUPPORTED
+    c = eco.eco_step_constants(eco.make_hparams(mode=eco.ECO_MODE_MASTER))
+    assert c.kappa == 0 and c.alpha == 0 and c.inv_lr == 0
 
 
 def test_product_package_never_reaches_the_oracle():

@@ -152,10 +152,8 @@ def test_variants_on_ragged_tensors(harness, o32, fmt, opt, rnd, inject, wd):
 
 
 def _run_with_layout(harness, o32, wl, steps, over):
-    from paper_2601_22101_amd import binding as eco
-    dw = harness.DeviceWorkload(wl, DEV)
-    dw.plan.close()
-    dw.plan = eco.Plan([dw.descriptor(tv) for tv in dw.tensors], dw.hparams(1, **over))
+    dw = harness.DeviceWorkload(wl, DEV, layout=over)
+    over = {}
     host = [host_copy(tv) for tv in dw.tensors]
     worst = {}
     for k in range(1, steps + 1):
@@ -172,6 +170,43 @@ def _run_with_layout(harness, o32, wl, steps, over):
                 worst[key] = max(worst.get(key, 0), val)
     dw.close()
     return worst
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
+@pytest.mark.parametrize("opt,mode,rnd", [(0, 3, 0), (0, 3, 1), (1, 3, 0), (1, 2, 0), (1, 2, 1)])
+def test_master_weight_and_exact_injection_modes(harness, o32, fmt, opt, mode, rnd):
+    """ECO_MODE_MASTER (fp32 master copy, Sec. 3.1) and ECO_MODE_EXACT (stored error, Appendix A) on ragged tensors."""
+    wl = small_mixed_workload(fmt)
+    over = dict(opt=opt, mode=mode, round=rnd)
+    if opt == 1:
+        over["lr"] = 0.05
+    worst = _run_with_layout(harness, o32, wl, 4, over)
+    assert worst["code_mismatch"] == 0 and worst["aux_bit_mismatch"] == 0, worst
+
+
+def test_exact_injection_tracks_master_weights_on_the_device(harness, eco):
+    """Appendix A on the GPU: from the theorem's initial conditions the stored-error run and the master-weight
+    run see the same gradients and must keep (almost always) the same codes; theta^ + e tracks the master copy."""
+    wl = workloads.Workload("eq", [workloads.TensorSpec("w", (64, 1024))], steps=8, lr=0.05)
+    a = harness.DeviceWorkload(wl, DEV, layout=dict(opt=eco.ECO_OPT_SGDM, mode=eco.ECO_MODE_MASTER, round=eco.ECO_ROUND_RTN))
+    b = harness.DeviceWorkload(wl, DEV, layout=dict(opt=eco.ECO_OPT_SGDM, mode=eco.ECO_MODE_EXACT, round=eco.ECO_ROUND_RTN))
+    n = wl.numel
+    deq = torch.zeros(n, device=DEV)
+    b.tensors[0].m.copy_(-b.tensors[0].aux / (0.05 * wl.beta1))      # m_0 = m_0^MW - e_0/(eta beta), m_0^MW = 0
+    for k in range(1, 9):
+        a.fill_gradients(k)
+        b.fill_gradients(k)
+        a.step(k)
+        b.step(k)
+        torch.cuda.synchronize()
+        tb = b.tensors[0]
+        eco.eco_dequantize(tb.weights, tb.scales, n, 0, 128, 0, deq)
+        implicit_master = deq + tb.aux
+        torch.testing.assert_close(implicit_master, a.tensors[0].aux, rtol=0, atol=1e-5)
+        same = (a.tensors[0].weights == tb.weights).float().mean().item()
+        assert same > 0.99, same
+    a.close()
+    b.close()
 
 
 @pytest.mark.parametrize("fmt", ["fp8", "int4"])
@@ -305,7 +340,7 @@ def test_zero_gradient_and_zero_blocks(harness, eco, o32):
 def test_step_rejects_a_layout_that_differs_from_the_plan(harness, eco):
     wl = workloads.Workload("tiny", [workloads.TensorSpec("w", (4096,))], steps=1)
     dw = harness.DeviceWorkload(wl, DEV)
-    for over in (dict(block_size=64), dict(state_dtype=1), dict(scale_dtype=1), dict(opt=1)):
+    for over in (dict(block_size=64), dict(state_dtype=1), dict(scale_dtype=1), dict(opt=1), dict(mode=0)):
         with pytest.raises(eco.EcoError) as ei:
             dw.plan.step(dw.hparams(1, **over))
         assert ei.value.status == eco.ECO_EINVAL
