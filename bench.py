@@ -28,20 +28,25 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
 BYTES_PER_PARAM = {"fp8": 20.0625, "int4": 11.03125, "bf16_plain": 22.0}
 
 
-def algorithmic_bytes(wl) -> float:
+def algorithmic_bytes(wl, variant: str = "adam-sr") -> float:
+    """Bytes the method itself must move in one step (read + write), summed over the tensors."""
+    adam = variant.startswith("adam")
+    master = "master" in variant
+    exact = "exact" in variant
     total = 0.0
     for t in wl.tensors:
-        if t.fmt == "fp8":
-            sb = 2 if wl.scale_bf16 else 4
-            st = 2 if wl.state_bf16 else 4
-            total += t.numel * (2 * 1 + 2 + 4 * st + 2 * sb / wl.block_size)
-        elif t.fmt == "int4":
-            sb = 2 if wl.scale_bf16 else 4
-            st = 2 if wl.state_bf16 else 4
-            total += t.numel * (2 * 0.5 + 2 + 4 * st + 2 * sb / wl.block_size)
+        st = 2 if wl.state_bf16 else 4
+        state = (2 if adam else 1) * 2 * st                      # m (and v): read + write
+        if t.fmt in ("fp8", "int4"):
+            code = 1.0 if t.fmt == "fp8" else 0.5
+            sb = (2 if wl.scale_bf16 else 4) / wl.block_size
+            if master:                                             # master read+write, codes and scales written only
+                per = 2 * 4 + code + sb + 2 + state
+            else:
+                per = 2 * code + 2 * sb + 2 + state + (2 * 4 if exact else 0)
         else:
-            st = 2 if wl.state_bf16 else 4
-            total += t.numel * (2 * 2 + 2 + 4 * st)
+            per = 2 * 2 + 2 + state
+        total += t.numel * per
     return total
 
 
@@ -127,8 +132,12 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="workload number (1-5) of the baseline's configs")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning: workgroups per compute unit (0 = default)")
     ap.add_argument("--lds-bytes", type=int, default=-1, help="launch tuning: dynamic LDS per workgroup (-1 = default)")
-    ap.add_argument("--variant", default="adam-sr", choices=["adam-sr", "adam-rtn", "sgdm-sr", "sgdm-rtn"],
-                    help="optimizer / rounding variant of the step (the headline metric is adam-sr)")
+    ap.add_argument("--variant", default="adam-sr",
+                    choices=["adam-sr", "adam-rtn", "sgdm-sr", "sgdm-rtn", "adam-naive-sr", "adam-master-sr",
+                             "adam-master-rtn", "sgdm-master-sr", "sgdm-exact-sr"],
+                    help="optimizer / mode / rounding variant of the step (the headline metric is adam-sr = Adam-ECO "
+                         "with stochastic rounding; 'master' is the fp32-master-weight baseline, 'exact' the "
+                         "stored-error injection of Appendix A, 'naive' master weights removed without injection)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
@@ -163,6 +172,12 @@ def main() -> int:
         over["opt"] = eco.ECO_OPT_SGDM
     if args.variant.endswith("rtn"):
         over["round"] = eco.ECO_ROUND_RTN
+    if "master" in args.variant:
+        over["mode"] = eco.ECO_MODE_MASTER
+    elif "exact" in args.variant:
+        over["mode"] = eco.ECO_MODE_EXACT
+    elif "naive" in args.variant:
+        over["mode"] = eco.ECO_MODE_NAIVE
     t_setup = time.perf_counter()
     dw = harness.DeviceWorkload(wl, "cuda:0", layout=over)
     torch.cuda.synchronize()
@@ -195,7 +210,7 @@ def main() -> int:
     ms_per_step = wall / args.steps * 1e3
     value = wl.numel / (ms_per_step * 1e-3)
     avg_kernel_s = sum(kernel_ms) / len(kernel_ms) * 1e-3
-    alg_bytes = algorithmic_bytes(wl)
+    alg_bytes = algorithmic_bytes(wl, args.variant)
     achieved = alg_bytes / avg_kernel_s / 1e9
     out = {
         "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -204,10 +219,10 @@ def main() -> int:
         "config": {"workload": wl.name, "tensors": len(wl.tensors), "parameters": wl.numel,
                    "format": "fp8_e4m3 codes, block-128 fp32 scales, bf16 gradients, fp32 m and v"
                    if args.config != 5 else "int4 codes, group-128 bf16 scales, bf16 gradients, bf16 m and v",
-                   "optimizer": {"adam-sr": "Adam-ECO, stochastic rounding", "adam-rtn": "Adam-ECO, round to nearest",
-                                 "sgdm-sr": "SGDM-ECO, stochastic rounding", "sgdm-rtn": "SGDM-ECO, round to nearest"}[args.variant], "launches_per_step": 1 if args.config != 2 else 2},
+                   "optimizer": args.variant, "launches_per_step": 1 if args.config != 2 else 2},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": profiled_traffic(wl.name),
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": profiled_traffic(wl.name) if args.variant == "adam-sr" else None,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": avg_kernel_s * 1e3},
     }
     dw.close()

@@ -83,7 +83,7 @@ typedef enum {
                            to the master copy, weights = q(master), m is left alone                               */
 } eco_mode_t;
 
-/* One parameter tensor, flattened row-major.  Element i belongs to scale group i / block_size;
+/* One parameter tensor, flattened row-major.  Element i belongs to scale group i / group_size;
  * the last group may be shorter.  All pointers: device memory, 16-byte aligned. */
 typedef struct eco_tensor {
   void *weights;        /* FP8: numel bytes; INT4: ceil(numel/2) bytes; BF16_PLAIN: numel bf16; FP32_IDENTITY: numel fp32 */
@@ -94,6 +94,10 @@ typedef struct eco_tensor {
   void *aux;            /* numel fp32: ECO_MODE_EXACT: the stored error e_t (in: e_t, out: e_{t+1});
                            ECO_MODE_MASTER: the master weights (in place); ignored (may be NULL) in the other modes        */
   uint64_t numel;       /* > 0                                                                                             */
+  uint64_t group_size;  /* elements per scale group (Sec. 3.1 "granularity"); 0 = hparams.block_size.  Supported: powers
+                           of two in [32, 512] (block-wise); any multiple of 8 up to 8192 (e.g. the row length: row-wise
+                           scaling as in Sec. 4.1); >= numel (one scale for the tensor, as in Sec. 4.4).  The number of
+                           scales is ceil(numel / group_size); ignored for the unquantized formats                         */
   uint32_t tensor_id;   /* enters the random-number counter; keep it stable across steps and distinct across tensors      */
   int32_t fmt;          /* eco_format_t                                                                                    */
 } eco_tensor_t;
@@ -103,7 +107,7 @@ typedef struct eco_hparams {
   int32_t opt;            /* eco_opt_t                                                                     */
   int32_t round;          /* eco_round_t: rounding used when re-quantizing                                 */
   int32_t mode;           /* eco_mode_t; 1 = ECO                                                           */
-  uint32_t block_size;    /* elements per scale group: 32, 64, 128, 256 or 512                             */
+  uint32_t block_size;    /* default scale group of the plan's tensors: 32, 64, 128, 256 or 512 elements   */
   int32_t state_dtype;    /* eco_dtype_t of m and v (math is fp32; bf16 state is rounded to nearest even)  */
   int32_t scale_dtype;    /* eco_dtype_t of the scales                                                     */
   double lr;              /* eta  (> 0 when the mode injects)                                              */
@@ -138,8 +142,8 @@ typedef struct eco_plan eco_plan_t;
  *   layout     : HOST; only block_size, state_dtype, scale_dtype, opt and mode are read (they fix the
  *                memory layout the descriptors are checked against)
  *   out        : receives the plan; owned by the library until eco_plan_destroy
- * Allocates device memory for the tables (about 64 bytes per tensor + 4 bytes per 512 elements) and
- * copies them synchronously.  Errors: ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_ENOMEM, ECO_EHIP.
+ * Allocates device memory for the tables (80 bytes per tensor + 4 bytes per 512 elements, or per scale group
+ * for groups wider than 512) and copies them synchronously.  Errors: ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_ENOMEM, ECO_EHIP.
  */
 eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *layout, eco_plan_t **out);
 
@@ -148,7 +152,9 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan);
 
 /*
  * eco_step — one ECO step (Alg. 1 with Alg. 3 or Alg. 2) over every tensor of the plan.
- * Asynchronous on `stream`; allocates nothing; one kernel launch per storage format present.
+ * Asynchronous on `stream`; allocates nothing.  Launches per storage format present: one kernel over the full
+ * 512-element tiles of block-scaled tensors, one over their ragged tails if any, one per workgroup size for wide
+ * groups, and three for tensors with a single scale (abs-max pass, apply pass, scale write).
  * hp->block_size, state_dtype, scale_dtype, opt and mode must equal the plan's.
  */
 eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream);
@@ -163,13 +169,16 @@ eco_status_t eco_step_tensors(const eco_tensor_t *tensors, size_t n, const eco_h
  * eco_quantize_init — q(x) of Sec. 3.1 with round-to-nearest-even, for setting up quantized weights.
  *   src    : device, numel values of src_dtype (ECO_DT_FP32 or ECO_DT_BF16)
  *   weights, scales : device outputs, laid out as in eco_tensor_t
- * fmt must be ECO_FMT_FP8_E4M3 or ECO_FMT_INT4.  Asynchronous on `stream`.
+ * fmt must be ECO_FMT_FP8_E4M3 or ECO_FMT_INT4; group_size as in eco_tensor_t (not 0).  Asynchronous on `stream`.
+ * With one scale for a tensor of more than 8192 elements the abs-max is kept in a library-owned slot between
+ * the call's kernels: such calls must not overlap each other on different streams.
  */
-eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint32_t block_size,
+eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint64_t group_size,
                                int32_t scale_dtype, void *weights, void *scales, void *stream);
 
-/* eco_dequantize — dst[i] = dec(code_i) * scale[i / block_size] as fp32 (Sec. 3.1, x^ = s*y).  Asynchronous. */
-eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint32_t block_size,
+/* eco_dequantize — dst[i] = dec(code_i) * scale[i / group_size] as fp32 (Sec. 3.1, x^ = s*y); group_size >= 8.
+ * Asynchronous. */
+eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint64_t group_size,
                             int32_t scale_dtype, float *dst, void *stream);
 
 /*

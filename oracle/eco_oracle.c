@@ -356,7 +356,7 @@ int oracle_eco_step(const oracle_cfg *cfg, uint64_t numel, uint8_t *codes, REAL 
   if (quantized && (!codes || !scales)) return -1;
   if (!quantized && !wreal) return -1;
   if (fmt == FMT_ADDNOISE && !xi) return -1;
-  if (fmt == FMT_INT4 && (bs & 1)) return -1;
+  if (fmt == FMT_INT4 && (bs & 1) && (uint64_t)bs < numel) return -1;   /* two blocks would share a byte */
   if (cfg->elem_offset % (uint64_t)bs) return -1;
   if (!m || (adam && !v) || (!grad_bf16 && !grad_real)) return -1;
   if (mode < MODE_NAIVE || mode > MODE_MASTER) return -1;

@@ -24,8 +24,8 @@ ECO_MODE_NAIVE, ECO_MODE_ECO, ECO_MODE_EXACT, ECO_MODE_MASTER = 0, 1, 2, 3
 
 class eco_tensor_t(C.Structure):
     _fields_ = [("weights", C.c_void_p), ("scales", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p),
-                ("v", C.c_void_p), ("aux", C.c_void_p), ("numel", C.c_uint64), ("tensor_id", C.c_uint32),
-                ("fmt", C.c_int32)]
+                ("v", C.c_void_p), ("aux", C.c_void_p), ("numel", C.c_uint64), ("group_size", C.c_uint64),
+                ("tensor_id", C.c_uint32), ("fmt", C.c_int32)]
 
 
 class eco_hparams_t(C.Structure):
@@ -56,8 +56,8 @@ def _load() -> C.CDLL:
     lib.eco_plan_destroy.argtypes = [vp]
     lib.eco_step.argtypes = [vp, C.POINTER(eco_hparams_t), vp]
     lib.eco_step_tensors.argtypes = [C.POINTER(eco_tensor_t), C.c_size_t, C.POINTER(eco_hparams_t), vp]
-    lib.eco_quantize_init.argtypes = [vp, i32, u64, i32, u32, i32, vp, vp, vp]
-    lib.eco_dequantize.argtypes = [vp, vp, u64, i32, u32, i32, vp, vp]
+    lib.eco_quantize_init.argtypes = [vp, i32, u64, i32, u64, i32, vp, vp, vp]
+    lib.eco_dequantize.argtypes = [vp, vp, u64, i32, u64, i32, vp, vp]
     lib.eco_philox_fill.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     lib.eco_step_constants.argtypes = [C.POINTER(eco_hparams_t), C.POINTER(eco_constants_t)]
     lib.eco_set_option.argtypes = [i32, C.c_int64]
@@ -96,8 +96,10 @@ def _stream(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
-def make_tensor(weights, scales, grad, m, v, numel: int, tensor_id: int, fmt: int, aux=None) -> eco_tensor_t:
-    return eco_tensor_t(_ptr(weights), _ptr(scales), _ptr(grad), _ptr(m), _ptr(v), _ptr(aux), numel, tensor_id, fmt)
+def make_tensor(weights, scales, grad, m, v, numel: int, tensor_id: int, fmt: int, aux=None,
+                group_size: int = 0) -> eco_tensor_t:
+    return eco_tensor_t(_ptr(weights), _ptr(scales), _ptr(grad), _ptr(m), _ptr(v), _ptr(aux), numel, group_size,
+                        tensor_id, fmt)
 
 
 def make_hparams(*, opt=ECO_OPT_ADAM, round=ECO_ROUND_SR, inject=True, mode=None, block_size=128,
@@ -152,14 +154,14 @@ def eco_step_tensors(tensors: Sequence[eco_tensor_t], hp: eco_hparams_t, stream=
     _check(lib.eco_step_tensors(arr, len(tensors), C.byref(hp), _stream(stream)))
 
 
-def eco_quantize_init(src, src_dtype: int, numel: int, fmt: int, block_size: int, scale_dtype: int, weights, scales,
+def eco_quantize_init(src, src_dtype: int, numel: int, fmt: int, group_size: int, scale_dtype: int, weights, scales,
                       stream=None) -> None:
-    _check(lib.eco_quantize_init(_ptr(src), src_dtype, numel, fmt, block_size, scale_dtype, _ptr(weights),
+    _check(lib.eco_quantize_init(_ptr(src), src_dtype, numel, fmt, group_size, scale_dtype, _ptr(weights),
                                  _ptr(scales), _stream(stream)))
 
 
-def eco_dequantize(weights, scales, numel: int, fmt: int, block_size: int, scale_dtype: int, dst, stream=None) -> None:
-    _check(lib.eco_dequantize(_ptr(weights), _ptr(scales), numel, fmt, block_size, scale_dtype, _ptr(dst),
+def eco_dequantize(weights, scales, numel: int, fmt: int, group_size: int, scale_dtype: int, dst, stream=None) -> None:
+    _check(lib.eco_dequantize(_ptr(weights), _ptr(scales), numel, fmt, group_size, scale_dtype, _ptr(dst),
                               _stream(stream)))
 
 

@@ -35,17 +35,12 @@ eco_status_t fail_hip(hipError_t e, const char *what) {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int log2_exact(uint32_t x) {
-  for (int s = 0; s < 32; ++s)
-    if ((1u << s) == x) return s;
-  return -1;
-}
-
-eco_status_t check_block_size(uint32_t bs, int *shift) {
+// hparams.block_size is the default scale group of a plan: a power of two in [32, 512] (tensors may
+// override it with their own group_size)
+eco_status_t check_block_size(uint32_t bs) {
   if (bs == 0) return fail(ECO_EINVAL, "block_size must be positive");
-  const int s = log2_exact(bs);
+  const int s = eco::log2_exact(bs);
   if (s < 5 || s > 9) return fail(ECO_EUNSUPPORTED, "block_size %u: supported sizes are 32, 64, 128, 256, 512", bs);
-  *shift = s;
   return ECO_OK;
 }
 
@@ -100,12 +95,16 @@ void derive_constants(const eco_hparams_t *hp, eco_constants_t *c) {
   }
 }
 
-struct Group {
+struct Group {                           // the tensors of one storage format
   std::vector<eco::TensorDesc> descs;
-  std::vector<uint32_t> tile_tensor;     // one entry per full tile
-  std::vector<uint32_t> ragged_tensor;   // tensors whose last tile is partial
+  std::vector<uint32_t> tile_tensor;     // block-scaled: one entry per full tile
+  std::vector<uint32_t> ragged_tensor;   // block-scaled: tensors whose last tile is partial
+  std::vector<uint32_t> wide[eco::MAX_WIDE_WAVES + 1];   // wide groups, by waves per group: one entry per group
+  std::vector<uint32_t> tw_tile_tensor;  // tensor-wise: one entry per tile (full or partial)
+  std::vector<uint32_t> tw_tensor;       // tensor-wise: the tensors
   eco::TensorDesc *d_descs = nullptr;
-  uint32_t *d_tiles = nullptr;           // tile_tensor followed by ragged_tensor
+  uint32_t *d_tables = nullptr;          // all the lists above, back to back, then the abs-max slots
+  size_t off_ragged = 0, off_wide[eco::MAX_WIDE_WAVES + 1] = {0}, off_tw_tiles = 0, off_tw_tensor = 0, off_slots = 0;
 };
 
 int num_compute_units() {
@@ -113,6 +112,22 @@ int num_compute_units() {
   if (hipGetDevice(&dev) != hipSuccess) return 256;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
   return cus;
+}
+
+// Resident waves per compute unit at which the step kernel measured fastest on MI355X, by bytes moved per
+// 512-element tile (fp32 state: the kernel is bound by HBM, which delivers most with roughly 100-120 KB of
+// tile traffic in flight per compute unit; bf16 state: bound by instruction issue, no cap), expressed as
+// the dynamic-LDS request that produces the cap (160 KB of LDS per compute unit).
+uint32_t default_lds_bytes(const eco::KernelVariant &kv) {
+  if (kv.state_bf16 || kv.fmt == eco::FMT_BF16_PLAIN || kv.fmt == eco::FMT_FP32_ID) return 0;
+  int waves;
+  switch (kv.algo) {
+    case eco::ALGO_ADAM: waves = 12; break;          // 20.1 B/parameter
+    case eco::ALGO_ADAM_MASTER: waves = 8; break;    // 27.0
+    case eco::ALGO_SGDM: waves = 16; break;          // 12.1
+    default: waves = 12; break;                      // SGDM with master weights or stored error: 19-20
+  }
+  return static_cast<uint32_t>(163840 / waves / 512 * 512);
 }
 
 // Default: one workgroup per tile.  The hardware dispatcher then hands out tiles in address order,
@@ -133,7 +148,6 @@ unsigned grid_for(uint64_t tiles, int cus) {
 
 struct eco_plan {
   uint32_t block_size = 0;
-  int bs_shift = 0;
   int32_t state_dtype = 0, scale_dtype = 0, opt = 0, mode = 0;
   int cus = 256;
   Group groups[4];   // indexed by eco_format_t
@@ -182,7 +196,7 @@ eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out) {
 eco_status_t eco_plan_destroy(eco_plan_t *plan) {
   if (!plan) return ECO_OK;
   bool any = false;
-  for (Group &g : plan->groups) any = any || g.d_descs || g.d_tiles;
+  for (Group &g : plan->groups) any = any || g.d_descs || g.d_tables;
   eco_status_t st = ECO_OK;
   if (any) {
     const hipError_t e = hipDeviceSynchronize();
@@ -190,7 +204,7 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan) {
   }
   for (Group &g : plan->groups) {
     if (g.d_descs) (void)hipFree(g.d_descs);
-    if (g.d_tiles) (void)hipFree(g.d_tiles);
+    if (g.d_tables) (void)hipFree(g.d_tables);
   }
   delete plan;
   return st;
@@ -207,14 +221,12 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   if (layout->mode == ECO_MODE_EXACT && layout->opt != ECO_OPT_SGDM)
     return fail(ECO_EUNSUPPORTED, "exact stored-error injection is defined for SGDM only");
   const bool needs_aux = layout->mode == ECO_MODE_EXACT || layout->mode == ECO_MODE_MASTER;
-  int shift = 0;
-  eco_status_t st = check_block_size(layout->block_size, &shift);
+  eco_status_t st = check_block_size(layout->block_size);
   if (st != ECO_OK) return st;
 
   eco_plan *plan = new (std::nothrow) eco_plan;
   if (!plan) return fail(ECO_ENOMEM, "plan: host allocation failed");
   plan->block_size = layout->block_size;
-  plan->bs_shift = shift;
   plan->state_dtype = layout->state_dtype;
   plan->scale_dtype = layout->scale_dtype;
   plan->opt = layout->opt;
@@ -235,19 +247,43 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
         st = fail(ECO_EALIGN, "tensor %zu: every data pointer must be 16-byte aligned", i);
         break;
       }
+      const uint64_t gsz = t.group_size ? t.group_size : layout->block_size;
+      const int cls = quantized ? eco::classify_group(gsz, t.numel) : eco::GROUP_BLOCK;
+      if (cls == eco::GROUP_UNSUPPORTED) {
+        st = fail(ECO_EUNSUPPORTED, "tensor %zu: scale group of %llu elements: supported are powers of two in [32, 512], "
+                  "multiples of 8 up to 8192, and the whole tensor", i, (unsigned long long)gsz);
+        break;
+      }
       Group &g = plan->groups[t.fmt];
-      const uint64_t ntiles = t.numel / eco::TILE_ELEMS;   // full tiles
-      if (g.tile_tensor.size() + ntiles > 0xFFFFFFF0ull) { st = fail(ECO_EUNSUPPORTED, "plan: more than 2^32 tiles in one format"); break; }
       eco::TensorDesc d;
       std::memset(&d, 0, sizeof d);
       d.w = t.weights; d.s = t.scales; d.g = t.grad; d.m = t.m; d.v = t.v; d.aux = t.aux;
       d.numel = t.numel;
-      d.first_tile = static_cast<uint32_t>(g.tile_tensor.size());
       d.tensor_id = t.tensor_id;
       const uint32_t idx = static_cast<uint32_t>(g.descs.size());
+      uint64_t units = 0;                 // tiles or groups this tensor adds to its launch list
+      std::vector<uint32_t> *list = nullptr;
+      if (cls == eco::GROUP_BLOCK) {
+        d.group_size = quantized ? gsz : layout->block_size;
+        d.bs_shift = static_cast<uint32_t>(eco::log2_exact(d.group_size));
+        units = t.numel / eco::TILE_ELEMS;              // full tiles
+        list = &g.tile_tensor;
+        if (t.numel % eco::TILE_ELEMS) g.ragged_tensor.push_back(idx);
+      } else if (cls == eco::GROUP_WIDE) {
+        d.group_size = gsz < t.numel ? gsz : t.numel;
+        units = (t.numel + d.group_size - 1) / d.group_size;
+        list = &g.wide[(d.group_size + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS];
+      } else {
+        d.group_size = t.numel;
+        d.slot = static_cast<uint32_t>(g.tw_tensor.size());
+        units = (t.numel + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS;
+        list = &g.tw_tile_tensor;
+        g.tw_tensor.push_back(idx);
+      }
+      if (list->size() + units > 0x7FFFFFF0ull) { st = fail(ECO_EUNSUPPORTED, "plan: more than 2^31 tiles in one launch"); break; }
+      d.first_unit = static_cast<uint32_t>(list->size());
+      list->insert(list->end(), static_cast<size_t>(units), idx);
       g.descs.push_back(d);
-      g.tile_tensor.insert(g.tile_tensor.end(), static_cast<size_t>(ntiles), idx);
-      if (t.numel % eco::TILE_ELEMS) g.ragged_tensor.push_back(idx);
     }
   } catch (const std::bad_alloc &) {
     st = fail(ECO_ENOMEM, "plan: host allocation failed");
@@ -257,12 +293,30 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   plan->cus = num_compute_units();
   for (Group &g : plan->groups) {
     if (g.descs.empty()) continue;
+    // one device buffer: [full tiles | ragged | wide lists 1..16 | tensor-wise tiles | tensor-wise tensors | slots]
+    std::vector<uint32_t> host;
+    try {
+      host = g.tile_tensor;
+      g.off_ragged = host.size();
+      host.insert(host.end(), g.ragged_tensor.begin(), g.ragged_tensor.end());
+      for (int nw = 1; nw <= eco::MAX_WIDE_WAVES; ++nw) {
+        g.off_wide[nw] = host.size();
+        host.insert(host.end(), g.wide[nw].begin(), g.wide[nw].end());
+      }
+      g.off_tw_tiles = host.size();
+      host.insert(host.end(), g.tw_tile_tensor.begin(), g.tw_tile_tensor.end());
+      g.off_tw_tensor = host.size();
+      host.insert(host.end(), g.tw_tensor.begin(), g.tw_tensor.end());
+      g.off_slots = host.size();
+      host.insert(host.end(), g.tw_tensor.size() + 1, 0u);      // abs-max slots start at zero
+    } catch (const std::bad_alloc &) {
+      (void)eco_plan_destroy(plan);
+      return fail(ECO_ENOMEM, "plan: host allocation failed");
+    }
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&g.d_descs), g.descs.size() * sizeof(eco::TensorDesc));
-    const size_t nt = g.tile_tensor.size(), nr = g.ragged_tensor.size();
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&g.d_tiles), (nt + nr) * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&g.d_tables), host.size() * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemcpy(g.d_descs, g.descs.data(), g.descs.size() * sizeof(eco::TensorDesc), hipMemcpyHostToDevice);
-    if (e == hipSuccess && nt) e = hipMemcpy(g.d_tiles, g.tile_tensor.data(), nt * sizeof(uint32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess && nr) e = hipMemcpy(g.d_tiles + nt, g.ragged_tensor.data(), nr * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(g.d_tables, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       st = (e == hipErrorOutOfMemory) ? fail(ECO_ENOMEM, "plan: device allocation failed") : fail_hip(e, "plan upload");
       (void)eco_plan_destroy(plan);
@@ -286,22 +340,29 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
   for (int f = 0; f < 4; ++f) {
     Group &g = plan->groups[f];
     if (g.descs.empty()) continue;
+    if (!g.d_descs || !g.d_tables) return fail(ECO_EINVAL, "step: the plan's device tables are missing");
     eco::StepArgs a;
+    std::memset(&a, 0, sizeof a);
     a.tensors = g.d_descs;
-    a.tile_tensor = g.d_tiles;
-    a.ragged_tensor = g.d_tiles + g.tile_tensor.size();
+    a.tile_tensor = g.d_tables;
+    a.ragged_tensor = g.d_tables + g.off_ragged;
     a.num_tiles = static_cast<uint32_t>(g.tile_tensor.size());
     a.num_ragged = static_cast<uint32_t>(g.ragged_tensor.size());
-    a.bs_shift = static_cast<uint32_t>(plan->bs_shift);
+    a.wide_base = g.d_tables;
+    for (int nw = 1; nw <= eco::MAX_WIDE_WAVES; ++nw) {
+      a.wide_offset[nw] = static_cast<uint32_t>(g.off_wide[nw]);
+      a.num_wide[nw] = static_cast<uint32_t>(g.wide[nw].size());
+    }
+    a.tw_tile_tensor = g.d_tables + g.off_tw_tiles;
+    a.tw_tensor = g.d_tables + g.off_tw_tensor;
+    a.slots = g.d_tables + g.off_slots;
+    a.num_tw_tiles = static_cast<uint32_t>(g.tw_tile_tensor.size());
+    a.num_tw_tensors = static_cast<uint32_t>(g.tw_tensor.size());
     a.b1 = c.b1; a.omb1 = c.omb1; a.b2 = c.b2; a.omb2 = c.omb2; a.rbc2 = c.rbc2; a.c1 = c.c1; a.eps = c.eps;
     a.kappa = c.kappa; a.lr = c.lr; a.alpha = c.alpha; a.wd = c.wd; a.inv_lr = c.inv_lr; a.inv_lr_beta = c.inv_lr_beta;
     a.seed_lo = static_cast<uint32_t>(hp->seed);
     a.seed_hi = static_cast<uint32_t>(hp->seed >> 32);
     a.step_lo = static_cast<uint32_t>(hp->step);
-    // fp32 state: 20 B per parameter, bound by HBM -> cap the resident waves; bf16 state: 11-12 B per
-    // parameter, bound by vector-ALU issue -> full occupancy
-    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes)
-                                   : (hp->state_dtype == ECO_DT_FP32 ? eco::DEFAULT_STEP_LDS_BYTES : 0u);
     eco::KernelVariant kv;
     kv.fmt = f;
     kv.state_bf16 = hp->state_dtype == ECO_DT_BF16;
@@ -310,6 +371,7 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     else if (hp->mode == ECO_MODE_EXACT) kv.algo = eco::ALGO_SGDM_EXACT;
     else kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM : eco::ALGO_SGDM;
     kv.round = hp->round;
+    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes) : default_lds_bytes(kv);
     const hipError_t e = eco::launch_step(kv, a, grid_for(a.num_tiles, plan->cus), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "step kernel launch");
   }
@@ -330,41 +392,40 @@ eco_status_t eco_step_tensors(const eco_tensor_t *tensors, size_t n, const eco_h
   return st2;
 }
 
-static eco_status_t check_flat(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint32_t block_size,
-                               int32_t scale_dtype, int *shift) {
+static eco_status_t check_flat(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint64_t group_size,
+                               int32_t scale_dtype) {
   if (fmt != ECO_FMT_FP8_E4M3 && fmt != ECO_FMT_INT4) return fail(ECO_EINVAL, "format %d is not a quantized format", fmt);
   if (!is_dtype(scale_dtype)) return fail(ECO_EINVAL, "unknown scale dtype");
   if (numel == 0) return fail(ECO_EINVAL, "numel == 0");
+  if (group_size == 0) return fail(ECO_EINVAL, "group_size must be positive");
   if (!weights || !scales) return fail(ECO_EINVAL, "null weights or scales");
   if (!aligned16(weights) || !aligned16(scales)) return fail(ECO_EALIGN, "weights and scales must be 16-byte aligned");
-  return check_block_size(block_size, shift);
+  return ECO_OK;
 }
 
-eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint32_t block_size,
+eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint64_t group_size,
                                int32_t scale_dtype, void *weights, void *scales, void *stream) {
-  int shift = 0;
-  eco_status_t st = check_flat(weights, scales, numel, fmt, block_size, scale_dtype, &shift);
+  eco_status_t st = check_flat(weights, scales, numel, fmt, group_size, scale_dtype);
   if (st != ECO_OK) return st;
   if (!src) return fail(ECO_EINVAL, "null source");
   if (!is_dtype(src_dtype)) return fail(ECO_EINVAL, "unknown source dtype");
   if (!aligned16(src)) return fail(ECO_EALIGN, "source must be 16-byte aligned");
-  const uint64_t tiles = (numel + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS;
-  const hipError_t e = eco::launch_quantize_init(src, src_dtype == ECO_DT_BF16, numel, fmt, static_cast<uint32_t>(shift),
-                                                 scale_dtype == ECO_DT_BF16, weights, scales,
-                                                 grid_for(tiles, num_compute_units()), static_cast<hipStream_t>(stream));
+  if (eco::classify_group(group_size, numel) == eco::GROUP_UNSUPPORTED)
+    return fail(ECO_EUNSUPPORTED, "scale group of %llu elements: supported are powers of two in [32, 512], multiples of 8 "
+                "up to 8192, and the whole tensor", (unsigned long long)group_size);
+  const hipError_t e = eco::launch_quantize_init(src, src_dtype == ECO_DT_BF16, numel, fmt, group_size,
+                                                 scale_dtype == ECO_DT_BF16, weights, scales, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ECO_OK : fail_hip(e, "quantize kernel launch");
 }
 
-eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint32_t block_size,
+eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint64_t group_size,
                             int32_t scale_dtype, float *dst, void *stream) {
-  int shift = 0;
-  eco_status_t st = check_flat(weights, scales, numel, fmt, block_size, scale_dtype, &shift);
+  eco_status_t st = check_flat(weights, scales, numel, fmt, group_size, scale_dtype);
   if (st != ECO_OK) return st;
   if (!dst) return fail(ECO_EINVAL, "null destination");
   if (!aligned16(dst)) return fail(ECO_EALIGN, "destination must be 16-byte aligned");
-  const uint64_t tiles = (numel + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS;
-  const hipError_t e = eco::launch_dequantize(weights, scales, numel, fmt, static_cast<uint32_t>(shift),
-                                              scale_dtype == ECO_DT_BF16, dst, grid_for(tiles, num_compute_units()),
+  if (group_size < 8) return fail(ECO_EUNSUPPORTED, "scale groups of fewer than 8 elements are not supported");
+  const hipError_t e = eco::launch_dequantize(weights, scales, numel, fmt, group_size, scale_dtype == ECO_DT_BF16, dst,
                                               static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ECO_OK : fail_hip(e, "dequantize kernel launch");
 }

@@ -31,7 +31,10 @@ constexpr int TILE_ELEMS = WG_THREADS * ELEMS_PER_LANE;
 // state only: with bf16 state the step moves half the bytes and is bound by instruction issue.
 constexpr uint32_t DEFAULT_STEP_LDS_BYTES = 13312;
 
-struct TensorDesc {          // 64 bytes, device table entry
+constexpr int MAX_WIDE_WAVES = 16;          // widest single-workgroup scale group: 16 waves * 512 = 8192 elements
+constexpr uint64_t MAX_WIDE_GROUP = 8192;
+
+struct TensorDesc {          // 80 bytes, device table entry
   void *w;                   // weights / codes
   void *s;                   // scales
   const void *g;             // bf16 gradient
@@ -39,21 +42,30 @@ struct TensorDesc {          // 64 bytes, device table entry
   void *v;
   void *aux;                 // fp32: stored error (exact injection) or master weights
   uint64_t numel;
-  uint32_t first_tile;       // index of this tensor's first full tile in the group's tile list
+  uint64_t group_size;       // elements per scale group
+  uint32_t first_unit;       // index of this tensor's first tile (or first group) in its launch list
   uint32_t tensor_id;
+  uint32_t bs_shift;         // log2(group_size) for power-of-two groups of 32..512 elements
+  uint32_t slot;             // tensor-wise scaling: index of the tensor's abs-max slot
 };
-static_assert(sizeof(TensorDesc) == 64, "TensorDesc layout");
+static_assert(sizeof(TensorDesc) == 80, "TensorDesc layout");
 
 struct StepArgs {            // by-value kernel argument: everything wave-uniform
   const TensorDesc *tensors;
-  const uint32_t *tile_tensor;   // full tile -> index into tensors
-  const uint32_t *ragged_tensor; // tensors that end in a partial tile
-  uint32_t num_tiles;            // full tiles
-  uint32_t num_ragged;
-  uint32_t bs_shift;             // log2(block_size)
+  const uint32_t *tile_tensor;     // block-scaled tensors: full tile -> index into tensors
+  const uint32_t *ragged_tensor;   //   ... tensors that end in a partial tile
+  const uint32_t *wide_tensor;     // wide groups of the launch in flight: group -> index into tensors
+  const uint32_t *tw_tile_tensor;  // tensor-wise scaling: tile (full or partial) -> index into tensors
+  const uint32_t *tw_tensor;       //   ... the tensors themselves
+  uint32_t *slots;                 //   ... one abs-max slot (fp32 bit pattern) per such tensor, zero between steps
+  uint32_t num_tiles, num_ragged, num_tw_tiles, num_tw_tensors;
   float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd, inv_lr, inv_lr_beta;
   uint32_t seed_lo, seed_hi, step_lo;
-  uint32_t lds_bytes;            // host side only: dynamic LDS per workgroup of the step kernel
+  // host side only
+  uint32_t lds_bytes;              // dynamic LDS per workgroup of the full-tile kernel (occupancy cap)
+  const uint32_t *wide_base;       // wide-group lists, one per workgroup size, back to back
+  uint32_t wide_offset[MAX_WIDE_WAVES + 1];
+  uint32_t num_wide[MAX_WIDE_WAVES + 1];
 };
 
 struct KernelVariant {
@@ -66,10 +78,25 @@ struct KernelVariant {
 
 // Each launcher enqueues one kernel on `stream` and returns hipGetLastError().
 hipError_t launch_step(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream);
-hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, int fmt, uint32_t bs_shift,
-                                int scale_bf16, void *weights, void *scales, unsigned grid, hipStream_t stream);
-hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint32_t bs_shift,
-                             int scale_bf16, float *dst, unsigned grid, hipStream_t stream);
+hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, int fmt, uint64_t group_size,
+                                int scale_bf16, void *weights, void *scales, hipStream_t stream);
+hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint64_t group_size,
+                             int scale_bf16, float *dst, hipStream_t stream);
+
+// Scale-group classes (how the abs-max of a group is reduced)
+enum : int { GROUP_BLOCK = 0, GROUP_WIDE = 1, GROUP_TENSOR = 2, GROUP_UNSUPPORTED = -1 };
+inline int classify_group(uint64_t group_size, uint64_t numel) {
+  if (group_size >= 32 && group_size <= 512 && (group_size & (group_size - 1)) == 0) return GROUP_BLOCK;
+  const uint64_t g = group_size < numel ? group_size : numel;       // a group never exceeds the tensor
+  if (g <= MAX_WIDE_GROUP && g % 8 == 0) return GROUP_WIDE;
+  if (group_size >= numel) return GROUP_TENSOR;
+  return GROUP_UNSUPPORTED;
+}
+inline int log2_exact(uint64_t x) {
+  for (int s = 0; s < 64; ++s)
+    if ((1ull << s) == x) return s;
+  return -1;
+}
 hipError_t launch_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_word, uint64_t n_words,
                               uint32_t *dst, hipStream_t stream);
 

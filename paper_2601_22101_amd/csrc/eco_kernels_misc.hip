@@ -10,18 +10,14 @@ namespace eco {
 // nearest even, no injection (the method is applied to linear layers only; norm weights take the
 // ordinary optimizer).  FMT_FP32_ID: fp32 weights under the identity quantizer, for which the
 // quantization error is zero and Alg. 2/3 add nothing to the momentum.
-template <int FMT, bool STATE_BF16, bool ADAM, bool FULL>
+template <int FMT, bool STATE_BF16, bool ADAM, int ACC>
 __device__ __forceinline__ void plain_tile(const StepArgs &a, const TensorDesc &td, uint64_t e0) {
-  int nvalid = 8;
-  if (!FULL) {
-    const int64_t left = (int64_t)td.numel - (int64_t)e0;
-    nvalid = left >= 8 ? 8 : (left <= 0 ? 0 : (int)left);
-  }
+  const int nvalid = ACC == ACC_FULL ? 8 : valid_from(e0, td.numel);
   float w[8], g[8], m[8], v[8];
-  load_state8<FMT == FMT_BF16_PLAIN, FULL>(td.w, e0, nvalid, w);
-  load_bf16x8<FULL>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
-  load_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
-  if (ADAM) load_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
+  load_state8<FMT == FMT_BF16_PLAIN, ACC>(td.w, e0, nvalid, w);
+  load_bf16x8<ACC>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
+  load_state8<STATE_BF16, ACC>(td.m, e0, nvalid, m);
+  if (ADAM) load_state8<STATE_BF16, ACC>(td.v, e0, nvalid, v);
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     float wj = w[j];
@@ -37,35 +33,34 @@ __device__ __forceinline__ void plain_tile(const StepArgs &a, const TensorDesc &
     if (a.wd != 0.0f) wj = wj - a.wd * wj;
     w[j] = wj - u;
   }
-  store_state8<FMT == FMT_BF16_PLAIN, FULL>(td.w, e0, nvalid, w);
-  store_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
-  if (ADAM) store_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
+  store_state8<FMT == FMT_BF16_PLAIN, ACC>(td.w, e0, nvalid, w);
+  store_state8<STATE_BF16, ACC>(td.m, e0, nvalid, m);
+  if (ADAM) store_state8<STATE_BF16, ACC>(td.v, e0, nvalid, v);
 }
 
 template <int FMT, bool STATE_BF16, bool ADAM>
 __global__ __launch_bounds__(WG_THREADS) void eco_plain_kernel(const StepArgs a) {
   for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
-    const TensorDesc td = load_tensor_desc(a, load_tile_tensor(a, tile));
-    const uint64_t tile_off = (uint64_t)(tile - td.first_tile) * TILE_ELEMS;
-    plain_tile<FMT, STATE_BF16, ADAM, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+    const TensorDesc td = load_tensor_desc(a, load_table(a.tile_tensor, tile));
+    const uint64_t tile_off = (uint64_t)(tile - td.first_unit) * TILE_ELEMS;
+    plain_tile<FMT, STATE_BF16, ADAM, ACC_FULL>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
   }
 }
 
 template <int FMT, bool STATE_BF16, bool ADAM>
 __global__ __launch_bounds__(WG_THREADS) void eco_plain_ragged_kernel(const StepArgs a) {
-  const ECO_CONST_AS uint32_t *rt = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.ragged_tensor;
-  const TensorDesc td = load_tensor_desc(a, rt[blockIdx.x]);
+  const TensorDesc td = load_tensor_desc(a, load_table(a.ragged_tensor, blockIdx.x));
   const uint64_t tile_off = td.numel / TILE_ELEMS * TILE_ELEMS;
-  plain_tile<FMT, STATE_BF16, ADAM, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+  plain_tile<FMT, STATE_BF16, ADAM, ACC_GUARDED>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
 }
 
 hipError_t launch_step_plain(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(F, ST, OP)                                                                                  \
+#define ECO_LAUNCH(F, ST, AD)                                                                                  \
   do {                                                                                                         \
     if (args.num_tiles)                                                                                        \
-      hipLaunchKernelGGL((eco_plain_kernel<F, ST, OP>), dim3(grid), dim3(WG_THREADS), 0, stream, args);        \
+      hipLaunchKernelGGL((eco_plain_kernel<F, ST, AD>), dim3(grid), dim3(WG_THREADS), 0, stream, args);        \
     if (args.num_ragged)                                                                                       \
-      hipLaunchKernelGGL((eco_plain_ragged_kernel<F, ST, OP>), dim3(args.num_ragged), dim3(WG_THREADS), 0,     \
+      hipLaunchKernelGGL((eco_plain_ragged_kernel<F, ST, AD>), dim3(args.num_ragged), dim3(WG_THREADS), 0,     \
                          stream, args);                                                                        \
   } while (0)
   const int key = (kv.fmt == FMT_FP32_ID ? 4 : 0) | (kv.state_bf16 ? 2 : 0) | (algo_is_adam(kv.algo) ? 0 : 1);
@@ -90,100 +85,135 @@ hipError_t launch_step(const KernelVariant &kv, const StepArgs &args, unsigned g
 }
 
 // ------------------------------------------------------------------------ initial quantizer
-// q(x) of Sec. 3.1 with nearest-even rounding over one flat tensor.
-template <int FMT, bool SCALE_BF16, bool SRC_BF16, bool FULL>
-__device__ __forceinline__ void quantize_tile(const void *src, uint64_t numel, uint32_t bs_shift, void *weights,
-                                              void *scales, uint64_t e0) {
-  int nvalid = 8;
-  if (!FULL) {
-    const int64_t left = (int64_t)numel - (int64_t)e0;
-    nvalid = left >= 8 ? 8 : (left <= 0 ? 0 : (int)left);
-  }
+// q(x) of Sec. 3.1 with nearest-even rounding over one flat tensor, for the three classes of scale
+// groups (in-wave blocks, one workgroup per wide group, one scale for the whole tensor in two passes).
+// The two-pass form keeps its abs-max in one file-scope slot, so calls that use it must not overlap.
+__device__ uint32_t g_quantize_slot = 0;
+
+template <int FMT, bool SCALE_BF16, bool SRC_BF16, int ACC, int RED>
+__device__ __forceinline__ void quantize_lane(const void *src, void *weights, void *scales, uint64_t e0, int nvalid,
+                                              uint64_t sg, int shift, bool scale_writer) {
   float x[8];
-  load_state8<SRC_BF16, FULL>(src, e0, nvalid, x);
-  const float amax = u2f(group_umax(f2u(absmax8(x)), 1 << (bs_shift - 3)));
+  load_state8<SRC_BF16, ACC>(src, e0, nvalid, x);
+  const float amax = group_absmax<RED>(absmax8(x), shift, &g_quantize_slot);
+  if (RED == RED_ATOMIC) return;
   float s_new, inv;
   block_scale<FMT, SCALE_BF16>(amax, s_new, inv);
   uint32_t c[2];
   const Philox4 none = {0, 0, 0, 0};
   encode8<FMT, ROUND_RTN, false>(x, inv, none, c);
-  store_codes8<FMT, FULL>(weights, e0, nvalid, c);
-  const uint64_t blk = e0 >> bs_shift;
-  const uint32_t lanes_mask = (1u << (bs_shift - 3)) - 1u;
-  if ((threadIdx.x & lanes_mask) == 0 && (FULL || nvalid > 0)) {
-    if (SCALE_BF16) static_cast<uint16_t *>(scales)[blk] = (uint16_t)(f2u(s_new) >> 16);
-    else static_cast<float *>(scales)[blk] = s_new;
+  store_codes8<FMT, ACC>(weights, e0, nvalid, c);
+  if (RED != RED_SLOT && scale_writer && (ACC == ACC_FULL || nvalid > 0)) {
+    if (SCALE_BF16) static_cast<uint16_t *>(scales)[sg] = (uint16_t)(f2u(s_new) >> 16);
+    else static_cast<float *>(scales)[sg] = s_new;
   }
 }
 
 template <int FMT, bool SCALE_BF16, bool SRC_BF16>
 __global__ __launch_bounds__(WG_THREADS) void eco_quantize_kernel(const void *src, uint64_t numel, uint32_t bs_shift,
                                                                   void *weights, void *scales) {
-  const uint64_t ntiles = (numel + TILE_ELEMS - 1) / TILE_ELEMS;
-  for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const uint64_t tile_off = tile * TILE_ELEMS;
-    const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-    if (tile_off + TILE_ELEMS <= numel) quantize_tile<FMT, SCALE_BF16, SRC_BF16, true>(src, numel, bs_shift, weights, scales, e0);
-    else quantize_tile<FMT, SCALE_BF16, SRC_BF16, false>(src, numel, bs_shift, weights, scales, e0);
+  const uint64_t e0 = (uint64_t)blockIdx.x * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  const bool writer = (threadIdx.x & ((1u << (bs_shift - 3)) - 1u)) == 0;
+  if ((uint64_t)(blockIdx.x + 1) * TILE_ELEMS <= numel)
+    quantize_lane<FMT, SCALE_BF16, SRC_BF16, ACC_FULL, RED_BLOCK>(src, weights, scales, e0, 8, e0 >> bs_shift, (int)bs_shift, writer);
+  else
+    quantize_lane<FMT, SCALE_BF16, SRC_BF16, ACC_GUARDED, RED_BLOCK>(src, weights, scales, e0, valid_from(e0, numel),
+                                                                     e0 >> bs_shift, (int)bs_shift, writer);
+}
+
+template <int FMT, bool SCALE_BF16, bool SRC_BF16>
+__global__ __launch_bounds__(1024) void eco_quantize_wide_kernel(const void *src, uint64_t numel, uint64_t group_size,
+                                                                 void *weights, void *scales) {
+  const uint64_t start = (uint64_t)blockIdx.x * group_size;
+  const uint64_t end = start + group_size < numel ? start + group_size : numel;
+  const uint64_t e0 = start + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  quantize_lane<FMT, SCALE_BF16, SRC_BF16, ACC_LANE, RED_WG>(src, weights, scales, e0, valid_from(e0, end), blockIdx.x, 0,
+                                                             threadIdx.x == 0);
+}
+
+template <int FMT, bool SCALE_BF16, bool SRC_BF16, int RED>
+__global__ __launch_bounds__(WG_THREADS) void eco_quantize_tensorwise_kernel(const void *src, uint64_t numel, void *weights,
+                                                                             void *scales) {
+  const uint64_t e0 = (uint64_t)blockIdx.x * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  quantize_lane<FMT, SCALE_BF16, SRC_BF16, ACC_LANE, RED>(src, weights, scales, e0, valid_from(e0, numel), 0, 0, false);
+}
+
+template <int FMT, bool SCALE_BF16>
+__global__ void eco_quantize_tensorwise_scale_kernel(void *scales) {
+  float s_new, inv;
+  block_scale<FMT, SCALE_BF16>(u2f(g_quantize_slot), s_new, inv);
+  if (SCALE_BF16) static_cast<uint16_t *>(scales)[0] = (uint16_t)(f2u(s_new) >> 16);
+  else static_cast<float *>(scales)[0] = s_new;
+  g_quantize_slot = 0;
+}
+
+template <int FMT, bool SC, bool SR>
+static void launch_quantize_t(const void *src, uint64_t numel, uint64_t group_size, void *weights, void *scales,
+                              hipStream_t stream) {
+  const uint64_t tiles = (numel + TILE_ELEMS - 1) / TILE_ELEMS;
+  const int cls = classify_group(group_size, numel);
+  if (cls == GROUP_BLOCK) {
+    hipLaunchKernelGGL((eco_quantize_kernel<FMT, SC, SR>), dim3((unsigned)tiles), dim3(WG_THREADS), 0, stream, src, numel,
+                       (uint32_t)log2_exact(group_size), weights, scales);
+  } else if (cls == GROUP_WIDE) {
+    const uint64_t g = group_size < numel ? group_size : numel;
+    const unsigned nw = (unsigned)((g + TILE_ELEMS - 1) / TILE_ELEMS);
+    hipLaunchKernelGGL((eco_quantize_wide_kernel<FMT, SC, SR>), dim3((unsigned)((numel + g - 1) / g)), dim3(64 * nw), 0,
+                       stream, src, numel, g, weights, scales);
+  } else {
+    hipLaunchKernelGGL((eco_quantize_tensorwise_kernel<FMT, SC, SR, RED_ATOMIC>), dim3((unsigned)tiles), dim3(WG_THREADS), 0,
+                       stream, src, numel, weights, scales);
+    hipLaunchKernelGGL((eco_quantize_tensorwise_kernel<FMT, SC, SR, RED_SLOT>), dim3((unsigned)tiles), dim3(WG_THREADS), 0,
+                       stream, src, numel, weights, scales);
+    hipLaunchKernelGGL((eco_quantize_tensorwise_scale_kernel<FMT, SC>), dim3(1), dim3(1), 0, stream, scales);
   }
 }
 
-hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, int fmt, uint32_t bs_shift, int scale_bf16,
-                                void *weights, void *scales, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(F, SC, SR)                                                                              \
-  hipLaunchKernelGGL((eco_quantize_kernel<F, SC, SR>), dim3(grid), dim3(WG_THREADS), 0, stream, src, numel, \
-                     bs_shift, weights, scales)
+hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, int fmt, uint64_t group_size, int scale_bf16,
+                                void *weights, void *scales, hipStream_t stream) {
   const int key = (fmt == FMT_INT4 ? 4 : 0) | (scale_bf16 ? 2 : 0) | (src_bf16 ? 1 : 0);
   switch (key) {
-    case 0: ECO_LAUNCH(FMT_FP8, false, false); break;
-    case 1: ECO_LAUNCH(FMT_FP8, false, true); break;
-    case 2: ECO_LAUNCH(FMT_FP8, true, false); break;
-    case 3: ECO_LAUNCH(FMT_FP8, true, true); break;
-    case 4: ECO_LAUNCH(FMT_INT4, false, false); break;
-    case 5: ECO_LAUNCH(FMT_INT4, false, true); break;
-    case 6: ECO_LAUNCH(FMT_INT4, true, false); break;
-    default: ECO_LAUNCH(FMT_INT4, true, true); break;
+    case 0: launch_quantize_t<FMT_FP8, false, false>(src, numel, group_size, weights, scales, stream); break;
+    case 1: launch_quantize_t<FMT_FP8, false, true>(src, numel, group_size, weights, scales, stream); break;
+    case 2: launch_quantize_t<FMT_FP8, true, false>(src, numel, group_size, weights, scales, stream); break;
+    case 3: launch_quantize_t<FMT_FP8, true, true>(src, numel, group_size, weights, scales, stream); break;
+    case 4: launch_quantize_t<FMT_INT4, false, false>(src, numel, group_size, weights, scales, stream); break;
+    case 5: launch_quantize_t<FMT_INT4, false, true>(src, numel, group_size, weights, scales, stream); break;
+    case 6: launch_quantize_t<FMT_INT4, true, false>(src, numel, group_size, weights, scales, stream); break;
+    default: launch_quantize_t<FMT_INT4, true, true>(src, numel, group_size, weights, scales, stream); break;
   }
-#undef ECO_LAUNCH
   return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------ dequantizer
-template <int FMT, bool SCALE_BF16, bool FULL>
-__device__ __forceinline__ void dequantize_tile(const void *weights, const void *scales, uint64_t numel,
-                                                uint32_t bs_shift, float *dst, uint64_t e0) {
-  int nvalid = 8;
-  if (!FULL) {
-    const int64_t left = (int64_t)numel - (int64_t)e0;
-    nvalid = left >= 8 ? 8 : (left <= 0 ? 0 : (int)left);
-  }
-  uint32_t c[2];
-  load_codes8<FMT, FULL>(weights, e0, nvalid, c);
-  const float s = (FULL || nvalid > 0) ? load_scale<SCALE_BF16>(scales, e0 >> bs_shift) : 0.0f;
-  float x[8];
-  x[0] = decode_elem<FMT, 0>(c) * s; x[1] = decode_elem<FMT, 1>(c) * s; x[2] = decode_elem<FMT, 2>(c) * s;
-  x[3] = decode_elem<FMT, 3>(c) * s; x[4] = decode_elem<FMT, 4>(c) * s; x[5] = decode_elem<FMT, 5>(c) * s;
-  x[6] = decode_elem<FMT, 6>(c) * s; x[7] = decode_elem<FMT, 7>(c) * s;
-  store_f32x8<FULL>(dst + e0, nvalid, x);
-}
-
+// dst[i] = dec(code_i) * scale[i / group_size]; a lane's 8 elements may straddle two groups when the
+// group size is not a multiple of 8, so the scale index is taken per element.
 template <int FMT, bool SCALE_BF16>
 __global__ __launch_bounds__(WG_THREADS) void eco_dequantize_kernel(const void *weights, const void *scales,
-                                                                    uint64_t numel, uint32_t bs_shift, float *dst) {
-  const uint64_t ntiles = (numel + TILE_ELEMS - 1) / TILE_ELEMS;
-  for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const uint64_t tile_off = tile * TILE_ELEMS;
-    const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-    if (tile_off + TILE_ELEMS <= numel) dequantize_tile<FMT, SCALE_BF16, true>(weights, scales, numel, bs_shift, dst, e0);
-    else dequantize_tile<FMT, SCALE_BF16, false>(weights, scales, numel, bs_shift, dst, e0);
-  }
+                                                                    uint64_t numel, uint64_t group_size, float *dst) {
+  const uint64_t e0 = (uint64_t)blockIdx.x * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  const int nvalid = valid_from(e0, numel);
+  if (nvalid == 0) return;
+  uint32_t c[2];
+  load_codes8<FMT, ACC_LANE>(weights, e0, nvalid, c);
+  const uint64_t sg = e0 / group_size;
+  const uint64_t boundary = (sg + 1) * group_size - e0;     // elements of this lane before the next group starts
+  const float s0 = load_scale<SCALE_BF16>(scales, sg);
+  const float s1 = boundary < (uint64_t)nvalid ? load_scale<SCALE_BF16>(scales, sg + 1) : s0;
+  float x[8];
+  x[0] = decode_elem<FMT, 0>(c); x[1] = decode_elem<FMT, 1>(c); x[2] = decode_elem<FMT, 2>(c); x[3] = decode_elem<FMT, 3>(c);
+  x[4] = decode_elem<FMT, 4>(c); x[5] = decode_elem<FMT, 5>(c); x[6] = decode_elem<FMT, 6>(c); x[7] = decode_elem<FMT, 7>(c);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) x[j] *= ((uint64_t)j < boundary ? s0 : s1);
+  store_f32x8<ACC_LANE>(dst + e0, nvalid, x);
 }
 
-hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint32_t bs_shift,
-                             int scale_bf16, float *dst, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(F, SC)                                                                                  \
-  hipLaunchKernelGGL((eco_dequantize_kernel<F, SC>), dim3(grid), dim3(WG_THREADS), 0, stream, weights, scales, \
-                     numel, bs_shift, dst)
+hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint64_t group_size,
+                             int scale_bf16, float *dst, hipStream_t stream) {
+  const unsigned tiles = (unsigned)((numel + TILE_ELEMS - 1) / TILE_ELEMS);
+#define ECO_LAUNCH(F, SC)                                                                                            \
+  hipLaunchKernelGGL((eco_dequantize_kernel<F, SC>), dim3(tiles), dim3(WG_THREADS), 0, stream, weights, scales, numel, \
+                     group_size, dst)
   if (fmt == FMT_FP8) { if (scale_bf16) ECO_LAUNCH(FMT_FP8, true); else ECO_LAUNCH(FMT_FP8, false); }
   else { if (scale_bf16) ECO_LAUNCH(FMT_INT4, true); else ECO_LAUNCH(FMT_INT4, false); }
 #undef ECO_LAUNCH

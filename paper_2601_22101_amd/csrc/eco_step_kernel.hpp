@@ -32,12 +32,22 @@ template <> struct FmtTraits<FMT_FP8> { static constexpr float RHO = 448.0f; };
 template <> struct FmtTraits<FMT_INT4> { static constexpr float RHO = 7.0f; };
 
 // ------------------------------------------------------------------ 8-element loads and stores
-// FULL: all 8 elements exist (vector access).  Otherwise only the first `nvalid` (possibly <= 0)
-// exist: element-wise access, missing elements read as zero and are not written.
+// Access modes of a lane's 8 consecutive elements:
+//   ACC_FULL    all 8 exist in every lane: vector access, no checks (full tiles)
+//   ACC_GUARDED only the first `nvalid` (possibly <= 0) exist: element-wise access in every lane; missing
+//               elements read as zero and are not written (the ragged tail of a tensor)
+//   ACC_LANE    decided per lane: vector access where nvalid == 8, element-wise elsewhere (wide groups,
+//               whose last lanes may lie beyond the group)
+enum : int { ACC_FULL = 0, ACC_GUARDED = 1, ACC_LANE = 2 };
 
-template <bool FULL>
+template <int ACC>
+__device__ __forceinline__ bool use_vector(int nvalid) {
+  return ACC == ACC_FULL || (ACC == ACC_LANE && nvalid == 8);
+}
+
+template <int ACC>
 __device__ __forceinline__ void load_f32x8(const float *p, int nvalid, float (&out)[8]) {
-  if (FULL) {
+  if (use_vector<ACC>(nvalid)) {
     const float4 a = reinterpret_cast<const float4 *>(p)[0];
     const float4 b = reinterpret_cast<const float4 *>(p)[1];
     out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
@@ -48,9 +58,9 @@ __device__ __forceinline__ void load_f32x8(const float *p, int nvalid, float (&o
   }
 }
 
-template <bool FULL>
+template <int ACC>
 __device__ __forceinline__ void load_bf16x8(const uint16_t *p, int nvalid, float (&out)[8]) {
-  if (FULL) {
+  if (use_vector<ACC>(nvalid)) {
     const uint4 q = *reinterpret_cast<const uint4 *>(p);
     out[0] = bf16_lo(q.x); out[1] = bf16_hi(q.x); out[2] = bf16_lo(q.y); out[3] = bf16_hi(q.y);
     out[4] = bf16_lo(q.z); out[5] = bf16_hi(q.z); out[6] = bf16_lo(q.w); out[7] = bf16_hi(q.w);
@@ -60,9 +70,9 @@ __device__ __forceinline__ void load_bf16x8(const uint16_t *p, int nvalid, float
   }
 }
 
-template <bool FULL>
+template <int ACC>
 __device__ __forceinline__ void store_f32x8(float *p, int nvalid, const float (&x)[8]) {
-  if (FULL) {
+  if (use_vector<ACC>(nvalid)) {
     reinterpret_cast<float4 *>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
     reinterpret_cast<float4 *>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
   } else {
@@ -72,12 +82,12 @@ __device__ __forceinline__ void store_f32x8(float *p, int nvalid, const float (&
   }
 }
 
-template <bool FULL>
+template <int ACC>
 __device__ __forceinline__ void store_bf16x8(uint16_t *p, int nvalid, const float (&x)[8]) {
   uint32_t h[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) h[j] = f32_to_bf16_rne(x[j]);
-  if (FULL) {
+  if (use_vector<ACC>(nvalid)) {
     *reinterpret_cast<uint4 *>(p) =
         make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
   } else {
@@ -87,23 +97,23 @@ __device__ __forceinline__ void store_bf16x8(uint16_t *p, int nvalid, const floa
   }
 }
 
-template <bool BF16, bool FULL>
+template <bool BF16, int ACC>
 __device__ __forceinline__ void load_state8(const void *base, uint64_t e0, int nvalid, float (&out)[8]) {
-  if (BF16) load_bf16x8<FULL>(static_cast<const uint16_t *>(base) + e0, nvalid, out);
-  else load_f32x8<FULL>(static_cast<const float *>(base) + e0, nvalid, out);
+  if (BF16) load_bf16x8<ACC>(static_cast<const uint16_t *>(base) + e0, nvalid, out);
+  else load_f32x8<ACC>(static_cast<const float *>(base) + e0, nvalid, out);
 }
 
-template <bool BF16, bool FULL>
+template <bool BF16, int ACC>
 __device__ __forceinline__ void store_state8(void *base, uint64_t e0, int nvalid, const float (&x)[8]) {
-  if (BF16) store_bf16x8<FULL>(static_cast<uint16_t *>(base) + e0, nvalid, x);
-  else store_f32x8<FULL>(static_cast<float *>(base) + e0, nvalid, x);
+  if (BF16) store_bf16x8<ACC>(static_cast<uint16_t *>(base) + e0, nvalid, x);
+  else store_f32x8<ACC>(static_cast<float *>(base) + e0, nvalid, x);
 }
 
 // 8 codes of one lane: two dwords of E4M3 bytes, or one dword of INT4 nibbles (in c[0]).
-template <int FMT, bool FULL>
+template <int FMT, int ACC>
 __device__ __forceinline__ void load_codes8(const void *base, uint64_t e0, int nvalid, uint32_t (&c)[2]) {
   const uint8_t *p = static_cast<const uint8_t *>(base) + (FMT == FMT_FP8 ? e0 : (e0 >> 1));
-  if (FULL) {
+  if (use_vector<ACC>(nvalid)) {
     if (FMT == FMT_FP8) {
       const uint2 q = *reinterpret_cast<const uint2 *>(p);
       c[0] = q.x; c[1] = q.y;
@@ -120,10 +130,10 @@ __device__ __forceinline__ void load_codes8(const void *base, uint64_t e0, int n
   }
 }
 
-template <int FMT, bool FULL>
+template <int FMT, int ACC>
 __device__ __forceinline__ void store_codes8(void *base, uint64_t e0, int nvalid, const uint32_t (&c)[2]) {
   uint8_t *p = static_cast<uint8_t *>(base) + (FMT == FMT_FP8 ? e0 : (e0 >> 1));
-  if (FULL) {
+  if (use_vector<ACC>(nvalid)) {
     if (FMT == FMT_FP8) *reinterpret_cast<uint2 *>(p) = make_uint2(c[0], c[1]);
     else *reinterpret_cast<uint32_t *>(p) = c[0];
   } else {
@@ -211,27 +221,56 @@ __device__ __forceinline__ void sqrt_plus_eps8(const float (&x)[8], float eps, f
   }
 }
 
-template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, bool FULL>
-__device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &td, uint64_t e0) {
+// ------------------------------------------------------------------ the step of one lane
+// How the abs-max of a scale group is obtained:
+//   RED_BLOCK  the group is 2^shift elements inside one wave: DPP/swizzle all-reduce over its lanes
+//   RED_WG     the group is the whole workgroup (1..16 waves): wave all-reduce, then an LDS combine
+//   RED_ATOMIC first pass of a group larger than a workgroup (tensor-wise scaling): wave all-reduce, one
+//              atomic max per wave into the group's slot of the plan's scratch; nothing else is written
+//   RED_SLOT   second pass: the abs-max is read from that slot; everything is recomputed and written
+//              except the scale (a third, tiny kernel writes it once every tile has used the old one)
+enum : int { RED_BLOCK = 0, RED_WG = 1, RED_ATOMIC = 2, RED_SLOT = 3 };
+
+template <int RED>
+__device__ __forceinline__ float group_absmax(float lane_max, int shift, uint32_t *slot) {
+  if (RED == RED_BLOCK) return u2f(group_umax(f2u(lane_max), 1 << (shift - 3)));
+  if (RED == RED_SLOT) return u2f(*slot);
+  const uint32_t wmax = group_umax(f2u(lane_max), 64);
+  if (RED == RED_ATOMIC) {
+    if ((threadIdx.x & 63) == 0) atomicMax(slot, wmax);
+    return 0.0f;
+  }
+  // RED_WG
+  __shared__ uint32_t wave_max[16];
+  const int nwaves = (int)(blockDim.x >> 6);
+  if (nwaves == 1) return u2f(wmax);
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = wmax;
+  __syncthreads();
+  uint32_t r = wave_max[0];
+  for (int k = 1; k < nwaves; ++k) { const uint32_t o = wave_max[k]; r = r > o ? r : o; }
+  return u2f(r);
+}
+
+// One lane's 8 consecutive elements, starting at element e0 of tensor td, of which the first nvalid exist;
+// scale group number sg; bs_shift = log2(group size) for RED_BLOCK.
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, int ACC, int RED>
+__device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &td, uint64_t e0, int nvalid,
+                                          uint64_t sg, bool scale_writer, uint32_t *slot) {
   constexpr bool ADAM = algo_is_adam(ALGO);
   constexpr bool MASTER = algo_is_master(ALGO);
-  int nvalid = 8;
-  if (!FULL) {
-    const int64_t left = (int64_t)td.numel - (int64_t)e0;
-    nvalid = left >= 8 ? 8 : (left <= 0 ? 0 : (int)left);
-  }
-  const uint64_t blk = e0 >> a.bs_shift;
+  constexpr bool WRITE = RED != RED_ATOMIC;       // the first pass of a two-pass group writes nothing
+  const bool any = ACC == ACC_FULL || nvalid > 0;
 
   float g[8], m[8], v[8], w[8];
-  load_bf16x8<FULL>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
-  load_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
-  if (ADAM) load_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);
+  load_bf16x8<ACC>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
+  load_state8<STATE_BF16, ACC>(td.m, e0, nvalid, m);
+  if (ADAM) load_state8<STATE_BF16, ACC>(td.v, e0, nvalid, v);
   if (MASTER) {
-    load_f32x8<FULL>(static_cast<const float *>(td.aux) + e0, nvalid, w);
+    load_f32x8<ACC>(static_cast<const float *>(td.aux) + e0, nvalid, w);
   } else {
     uint32_t c[2];
-    load_codes8<FMT, FULL>(td.w, e0, nvalid, c);
-    const float s_old = (FULL || nvalid > 0) ? load_scale<SCALE_BF16>(td.s, blk) : 0.0f;
+    load_codes8<FMT, ACC>(td.w, e0, nvalid, c);
+    const float s_old = any ? load_scale<SCALE_BF16>(td.s, sg) : 0.0f;
     w[0] = decode_elem<FMT, 0>(c) * s_old; w[1] = decode_elem<FMT, 1>(c) * s_old;
     w[2] = decode_elem<FMT, 2>(c) * s_old; w[3] = decode_elem<FMT, 3>(c) * s_old;
     w[4] = decode_elem<FMT, 4>(c) * s_old; w[5] = decode_elem<FMT, 5>(c) * s_old;
@@ -248,7 +287,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
       v[j] = fmaf(a.b2, v[j], a.omb2 * (g[j] * g[j]));
       x[j] = v[j] * a.rbc2;
     }
-    store_state8<STATE_BF16, FULL>(td.v, e0, nvalid, v);   // v is final (Alg. 3 returns it unchanged)
+    if (WRITE) store_state8<STATE_BF16, ACC>(td.v, e0, nvalid, v);   // v is final (Alg. 3 returns it unchanged)
     sqrt_plus_eps8(x, a.eps, d);
   }
 #pragma unroll
@@ -264,12 +303,13 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
     }
     if (a.wd != 0.0f) wj = wj - a.wd * wj;
     th[j] = wj - u;
-    if (!FULL && j >= nvalid) th[j] = 0.0f;
+    if (ACC != ACC_FULL && j >= nvalid) th[j] = 0.0f;
   }
-  if (MASTER) store_f32x8<FULL>(static_cast<float *>(td.aux) + e0, nvalid, th);
 
   // ECO_QUANTIZE
-  const float amax = u2f(group_umax(f2u(absmax8(th)), 1 << (a.bs_shift - 3)));
+  const float amax = group_absmax<RED>(absmax8(th), (int)td.bs_shift, slot);
+  if (!WRITE) return;
+  if (MASTER) store_f32x8<ACC>(static_cast<float *>(td.aux) + e0, nvalid, th);
   float s_new, inv;
   block_scale<FMT, SCALE_BF16>(amax, s_new, inv);
 
@@ -287,14 +327,14 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
   } else {
     encode8<FMT, ROUND, true>(th, inv, r, cn);
   }
-  store_codes8<FMT, FULL>(td.w, e0, nvalid, cn);
+  store_codes8<FMT, ACC>(td.w, e0, nvalid, cn);
 
   if (!MASTER) {
     float qn[8], eo[8];
     qn[0] = decode_elem<FMT, 0>(cn); qn[1] = decode_elem<FMT, 1>(cn); qn[2] = decode_elem<FMT, 2>(cn);
     qn[3] = decode_elem<FMT, 3>(cn); qn[4] = decode_elem<FMT, 4>(cn); qn[5] = decode_elem<FMT, 5>(cn);
     qn[6] = decode_elem<FMT, 6>(cn); qn[7] = decode_elem<FMT, 7>(cn);
-    if (ALGO == ALGO_SGDM_EXACT) load_f32x8<FULL>(static_cast<const float *>(td.aux) + e0, nvalid, eo);
+    if (ALGO == ALGO_SGDM_EXACT) load_f32x8<ACC>(static_cast<const float *>(td.aux) + e0, nvalid, eo);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const float e = th[j] - qn[j] * s_new;
@@ -302,15 +342,13 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
       else if (ALGO == ALGO_SGDM) m[j] = fmaf(a.alpha, e, m[j]);
       else { m[j] = fmaf(-a.inv_lr_beta, e, fmaf(a.inv_lr, eo[j], m[j])); eo[j] = e; }
     }
-    if (ALGO == ALGO_SGDM_EXACT) store_f32x8<FULL>(static_cast<float *>(td.aux) + e0, nvalid, eo);
+    if (ALGO == ALGO_SGDM_EXACT) store_f32x8<ACC>(static_cast<float *>(td.aux) + e0, nvalid, eo);
   }
-  store_state8<STATE_BF16, FULL>(td.m, e0, nvalid, m);
+  store_state8<STATE_BF16, ACC>(td.m, e0, nvalid, m);
 
-  // one lane per block stores the new scale
-  const uint32_t lanes_mask = (1u << (a.bs_shift - 3)) - 1u;
-  if ((threadIdx.x & lanes_mask) == 0 && (FULL || nvalid > 0)) {
-    if (SCALE_BF16) static_cast<uint16_t *>(td.s)[blk] = (uint16_t)(f2u(s_new) >> 16);
-    else static_cast<float *>(td.s)[blk] = s_new;
+  if (RED != RED_SLOT && scale_writer && any) {
+    if (SCALE_BF16) static_cast<uint16_t *>(td.s)[sg] = (uint16_t)(f2u(s_new) >> 16);
+    else static_cast<float *>(td.s)[sg] = s_new;
   }
 }
 
@@ -319,9 +357,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const TensorDesc &t
 // though the kernel also writes global memory.
 #define ECO_CONST_AS __attribute__((address_space(4)))
 
-__device__ __forceinline__ uint32_t load_tile_tensor(const StepArgs &a, uint32_t tile) {
-  const ECO_CONST_AS uint32_t *p = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.tile_tensor;
-  return p[tile];
+__device__ __forceinline__ uint32_t load_table(const uint32_t *table, uint32_t i) {
+  const ECO_CONST_AS uint32_t *p = (const ECO_CONST_AS uint32_t *)(uintptr_t)table;
+  return p[i];
 }
 
 __device__ __forceinline__ TensorDesc load_tensor_desc(const StepArgs &a, uint32_t ti) {
@@ -334,44 +372,109 @@ __device__ __forceinline__ TensorDesc load_tensor_desc(const StepArgs &a, uint32
   td.v = (void *)(uintptr_t)p[4];
   td.aux = (void *)(uintptr_t)p[5];
   td.numel = p[6];
-  const uint64_t ft = p[7];
-  td.first_tile = (uint32_t)ft;
-  td.tensor_id = (uint32_t)(ft >> 32);
+  td.group_size = p[7];
+  const uint64_t a8 = p[8], a9 = p[9];
+  td.first_unit = (uint32_t)a8;
+  td.tensor_id = (uint32_t)(a8 >> 32);
+  td.bs_shift = (uint32_t)a9;
+  td.slot = (uint32_t)(a9 >> 32);
   return td;
 }
 
-// Persistent kernel over the full tiles: workgroup b handles tiles b, b + gridDim.x, ...  The
-// tile -> tensor table and the tensor descriptors are wave-uniform and are fetched with scalar loads.
+// ------------------------------------------------------------------ kernels
+// (1) Block-scaled tensors (group = 32..512 elements, a power of two): one workgroup of one wave per
+// full 512-element tile, dispatched in address order (or, when the host caps the grid, looping with
+// the grid as stride).  The tile -> tensor table and the descriptors are wave-uniform scalar loads.
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(WG_THREADS, 8) void eco_step_kernel(const StepArgs a) {
   for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
-    const TensorDesc td = load_tensor_desc(a, load_tile_tensor(a, tile));
-    const uint64_t tile_off = (uint64_t)(tile - td.first_tile) * TILE_ELEMS;
-    step_tile<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, true>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+    const TensorDesc td = load_tensor_desc(a, load_table(a.tile_tensor, tile));
+    const uint64_t e0 = (uint64_t)(tile - td.first_unit) * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+    const bool writer = (threadIdx.x & ((1u << (td.bs_shift - 3)) - 1u)) == 0;
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED_BLOCK>(a, td, e0, 8, e0 >> td.bs_shift, writer, nullptr);
   }
 }
 
-// The last, partial tile of each tensor whose length is not a multiple of TILE_ELEMS: one workgroup
-// per such tensor, element-wise guarded accesses.  A separate kernel keeps the guards' registers and
-// branches out of the full-tile kernel.
+// (2) The last, partial tile of each block-scaled tensor whose length is not a multiple of TILE_ELEMS:
+// one workgroup per such tensor, element-wise guarded accesses.  A separate kernel keeps the guards'
+// registers and branches out of the full-tile kernel.
+__device__ __forceinline__ int valid_from(uint64_t e0, uint64_t end) {
+  const int64_t left = (int64_t)end - (int64_t)e0;
+  return left >= 8 ? 8 : (left <= 0 ? 0 : (int)left);
+}
+
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(WG_THREADS) void eco_step_ragged_kernel(const StepArgs a) {
-  const ECO_CONST_AS uint32_t *rt = (const ECO_CONST_AS uint32_t *)(uintptr_t)a.ragged_tensor;
-  const TensorDesc td = load_tensor_desc(a, rt[blockIdx.x]);
-  const uint64_t tile_off = td.numel / TILE_ELEMS * TILE_ELEMS;
-  step_tile<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, false>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
+  const TensorDesc td = load_tensor_desc(a, load_table(a.ragged_tensor, blockIdx.x));
+  const uint64_t e0 = td.numel / TILE_ELEMS * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  const bool writer = (threadIdx.x & ((1u << (td.bs_shift - 3)) - 1u)) == 0;
+  step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_GUARDED, RED_BLOCK>(a, td, e0, valid_from(e0, td.numel),
+                                                                              e0 >> td.bs_shift, writer, nullptr);
+}
+
+// (3) Wide groups (any multiple of 8 up to 8192 elements: row-wise scaling, Sec. 4.1): one workgroup of
+// ceil(group/512) waves per group, abs-max by wave all-reduce plus an LDS combine across the waves.
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
+__global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
+  const TensorDesc td = load_tensor_desc(a, load_table(a.wide_tensor, blockIdx.x));
+  const uint64_t grp = blockIdx.x - td.first_unit;
+  const uint64_t start = grp * td.group_size;
+  const uint64_t end = start + td.group_size < td.numel ? start + td.group_size : td.numel;
+  const uint64_t e0 = start + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_LANE, RED_WG>(a, td, e0, valid_from(e0, end), grp,
+                                                                        threadIdx.x == 0, nullptr);
+}
+
+// (4) One scale per tensor (tensor-wise scaling, Sec. 4.4), tensors too large for one workgroup: two passes
+// over 512-element tiles.  Pass 1 recomputes theta~ and folds its abs-max into the tensor's slot; pass 2
+// recomputes theta~ again (the inputs are untouched so far), quantizes against the slot's value and writes
+// codes and state; a last kernel writes the new scales and clears the slots.
+template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, int RED>
+__global__ __launch_bounds__(WG_THREADS) void eco_step_tensorwise_kernel(const StepArgs a) {
+  const TensorDesc td = load_tensor_desc(a, load_table(a.tw_tile_tensor, blockIdx.x));
+  const uint64_t e0 = (uint64_t)(blockIdx.x - td.first_unit) * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_LANE, RED>(a, td, e0, valid_from(e0, td.numel), 0, false,
+                                                                     a.slots + td.slot);
+}
+
+template <int FMT, bool SCALE_BF16>
+__global__ __launch_bounds__(WG_THREADS) void eco_tensorwise_scale_kernel(const StepArgs a) {
+  const uint32_t i = blockIdx.x * WG_THREADS + threadIdx.x;
+  if (i >= a.num_tw_tensors) return;
+  const TensorDesc td = load_tensor_desc(a, a.tw_tensor[i]);
+  float s_new, inv;
+  block_scale<FMT, SCALE_BF16>(u2f(a.slots[td.slot]), s_new, inv);
+  if (SCALE_BF16) static_cast<uint16_t *>(td.s)[0] = (uint16_t)(f2u(s_new) >> 16);
+  else static_cast<float *>(td.s)[0] = s_new;
+  a.slots[td.slot] = 0;
 }
 
 template <int FMT, bool STATE_BF16, bool SC, int RD>
 void launch_step_algos(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(AL)                                                                                      \
-  do {                                                                                                      \
-    if (args.num_tiles)                                                                                     \
-      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(grid), dim3(WG_THREADS),      \
-                         args.lds_bytes, stream, args);                                                     \
-    if (args.num_ragged)                                                                                    \
-      hipLaunchKernelGGL((eco_step_ragged_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_ragged),      \
-                         dim3(WG_THREADS), 0, stream, args);                                                \
+#define ECO_LAUNCH(AL)                                                                                            \
+  do {                                                                                                            \
+    if (args.num_tiles)                                                                                           \
+      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(grid), dim3(WG_THREADS),            \
+                         args.lds_bytes, stream, args);                                                           \
+    if (args.num_ragged)                                                                                          \
+      hipLaunchKernelGGL((eco_step_ragged_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_ragged),            \
+                         dim3(WG_THREADS), 0, stream, args);                                                      \
+    for (int nw = 1; nw <= MAX_WIDE_WAVES; ++nw) {                                                                \
+      if (!args.num_wide[nw]) continue;                                                                           \
+      StepArgs wa = args;                                                                                         \
+      wa.wide_tensor = args.wide_base + args.wide_offset[nw];                                                     \
+      hipLaunchKernelGGL((eco_step_wide_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_wide[nw]),            \
+                         dim3(64 * nw), 0, stream, wa);                                                           \
+    }                                                                                                             \
+    if (args.num_tw_tiles) {                                                                                      \
+      hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_ATOMIC>),                   \
+                         dim3(args.num_tw_tiles), dim3(WG_THREADS), 0, stream, args);                             \
+      hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_SLOT>),                     \
+                         dim3(args.num_tw_tiles), dim3(WG_THREADS), 0, stream, args);                             \
+      hipLaunchKernelGGL((eco_tensorwise_scale_kernel<FMT, SC>),                                                  \
+                         dim3((args.num_tw_tensors + WG_THREADS - 1) / WG_THREADS), dim3(WG_THREADS), 0, stream,  \
+                         args);                                                                                   \
+    }                                                                                                             \
   } while (0)
   switch (kv.algo) {
     case ALGO_ADAM: ECO_LAUNCH(ALGO_ADAM); break;

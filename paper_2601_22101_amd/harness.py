@@ -67,7 +67,8 @@ class DeviceWorkload:
             off += _round_up(t.numel, 512)
             if t.fmt in ("fp8", "int4"):
                 soffs.append(soff)
-                soff += _round_up((t.numel + bs - 1) // bs, 128)
+                gs = t.group_size(bs)
+                soff += _round_up((t.numel + gs - 1) // gs, 128)
                 coffs.append(code_bytes)
                 nbytes = t.numel if t.fmt == "fp8" else (t.numel + 1) // 2
                 code_bytes += _round_up(nbytes, 256)
@@ -93,7 +94,8 @@ class DeviceWorkload:
             if t.fmt in ("fp8", "int4"):
                 nbytes = n if t.fmt == "fp8" else (n + 1) // 2
                 w = self.codes[coffs[i]:coffs[i] + nbytes]
-                s = self.scales[soffs[i]:soffs[i] + (n + bs - 1) // bs]
+                gs = t.group_size(bs)
+                s = self.scales[soffs[i]:soffs[i] + (n + gs - 1) // gs]
             else:
                 w = self.plain[woffs[i]:woffs[i] + n]
                 s = None
@@ -111,7 +113,10 @@ class DeviceWorkload:
 
     def descriptor(self, tv: TensorViews) -> "eco.eco_tensor_t":
         return eco.make_tensor(tv.weights, tv.scales, tv.grad, tv.m, tv.v, tv.spec.numel, tv.tensor_id, tv.fmt,
-                               aux=tv.aux)
+                               aux=tv.aux, group_size=self.group_size(tv))
+
+    def group_size(self, tv: TensorViews) -> int:
+        return tv.spec.group_size(self.wl.block_size)
 
     def hparams(self, step: int, **over) -> "eco.eco_hparams_t":
         wl = self.wl
@@ -130,12 +135,12 @@ class DeviceWorkload:
             w = workloads.initial_weights(wl, tv.tensor_id, device=self.device, base_seed=self.base_seed)
             if tv.fmt in (eco.ECO_FMT_FP8_E4M3, eco.ECO_FMT_INT4):
                 sdt = eco.ECO_DT_BF16 if wl.scale_bf16 else eco.ECO_DT_FP32
-                eco.eco_quantize_init(w, eco.ECO_DT_FP32, tv.spec.numel, tv.fmt, wl.block_size, sdt, tv.weights,
-                                      tv.scales)
+                gs = self.group_size(tv)
+                eco.eco_quantize_init(w, eco.ECO_DT_FP32, tv.spec.numel, tv.fmt, gs, sdt, tv.weights, tv.scales)
                 if self.mode == eco.ECO_MODE_MASTER:
                     tv.aux.copy_(w)
                 elif self.mode == eco.ECO_MODE_EXACT:
-                    eco.eco_dequantize(tv.weights, tv.scales, tv.spec.numel, tv.fmt, wl.block_size, sdt, tv.aux)
+                    eco.eco_dequantize(tv.weights, tv.scales, tv.spec.numel, tv.fmt, gs, sdt, tv.aux)
                     torch.sub(w, tv.aux, out=tv.aux)            # e_0 = theta_0 - q(theta_0)
             else:
                 tv.weights.copy_(w.to(torch.bfloat16))

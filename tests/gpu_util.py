@@ -100,9 +100,9 @@ def _elements_of(byte_diff: np.ndarray, n: int) -> np.ndarray:
     return np.repeat(byte_diff, 2)[:n]
 
 
-def step_config(hp, tensor_id: int, fmt: int, elem_offset: int = 0) -> StepConfig:
-    """The oracle's view of the library's hyper-parameter struct."""
+def step_config(hp, tensor_id: int, fmt: int, elem_offset: int = 0, group_size: int = 0) -> StepConfig:
+    """The oracle's view of the library's hyper-parameter struct (group_size: the tensor's own scale group)."""
     return StepConfig(fmt=ORACLE_FMT[fmt], opt=hp.opt, round=hp.round, mode=hp.mode,
-                      block_size=hp.block_size, state_bf16=bool(hp.state_dtype), scale_bf16=bool(hp.scale_dtype),
+                      block_size=group_size or hp.block_size, state_bf16=bool(hp.state_dtype), scale_bf16=bool(hp.scale_dtype),
                       lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, weight_decay=hp.weight_decay,
                       step=hp.step, seed=hp.seed, elem_offset=elem_offset, tensor_id=tensor_id)

@@ -36,14 +36,14 @@ def test_every_declared_symbol_is_exported(eco):
 
 
 def test_struct_layouts_match_header(eco):
-    assert C.sizeof(eco.eco_tensor_t) == 64
+    assert C.sizeof(eco.eco_tensor_t) == 72
     assert C.sizeof(eco.eco_hparams_t) == 80
     assert C.sizeof(eco.eco_constants_t) == 52
 
 
 def _tensor(eco, **kw):
     base = dict(weights=0x1000, scales=0x2000, grad=0x3000, m=0x4000, v=0x5000, numel=4096, tensor_id=0,
-                fmt=eco.ECO_FMT_FP8_E4M3, aux=None)
+                fmt=eco.ECO_FMT_FP8_E4M3, aux=None, group_size=0)
     base.update(kw)
     return eco.make_tensor(**base)
 
@@ -78,6 +78,10 @@ def test_plan_validation_happens_before_any_device_work(eco):
                      (1024, eco.ECO_EUNSUPPORTED)):
         assert _status(eco, eco.eco_plan_create, [_tensor(eco)], eco.make_hparams(block_size=bs)) == want
     assert _status(eco, eco.eco_plan_create, [_tensor(eco)], eco.make_hparams(state_dtype=5)) == eco.ECO_EINVAL
+    # per-tensor scale groups: powers of two in [32, 512], multiples of 8 up to 8192, or the whole tensor
+    for gs in (100, 12, 1004):
+        assert _status(eco, eco.eco_plan_create, [_tensor(eco, group_size=gs)], hp) == eco.ECO_EUNSUPPORTED, gs
+    assert _status(eco, eco.eco_plan_create, [_tensor(eco, numel=20000, group_size=9000)], hp) == eco.ECO_EUNSUPPORTED
     # the master-weight and exact-injection modes need the aux buffer, aligned
     for mode, opt in ((eco.ECO_MODE_MASTER, eco.ECO_OPT_ADAM), (eco.ECO_MODE_EXACT, eco.ECO_OPT_SGDM)):
         hp2 = eco.make_hparams(mode=mode, opt=opt)
@@ -112,7 +116,8 @@ def test_flat_helpers_validate(eco):
     assert q(src=None) == eco.ECO_EINVAL
     assert q(w=None) == eco.ECO_EINVAL
     assert q(fmt=2) == eco.ECO_EINVAL
-    assert q(bs=48) == eco.ECO_EUNSUPPORTED
+    assert q(bs=100) == eco.ECO_EUNSUPPORTED
+    assert q(bs=0) == eco.ECO_EINVAL
     assert q(src=0x1004) == eco.ECO_EALIGN
     assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 1024, 0, 128, 0, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 0, 0x1000, 0) == eco.ECO_EINVAL

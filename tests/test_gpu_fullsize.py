@@ -69,7 +69,7 @@ def run_fullsize(wl, steps, n_tensors, seed):
         torch.cuda.synchronize()
         for (i, b0, n), (h, numel) in zip(spans, before):
             tv = dw.tensors[i]
-            oracle_step(o32, h, numel, step_config(hp, tv.tensor_id, tv.fmt, elem_offset=b0 * wl.block_size))
+            oracle_step(o32, h, numel, step_config(hp, tv.tensor_id, tv.fmt, elem_offset=b0 * wl.block_size))  # block-128 workloads
             after, _ = grab(tv, wl, b0, n)
             after["grad"] = h["grad"]
             st = compare(after, h, f"{wl.name} step {k} {tv.spec.name} blocks {b0}+{n}", wl.state_bf16)

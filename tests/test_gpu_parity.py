@@ -96,7 +96,7 @@ def run_workload_parity(harness, o32, wl, steps, base_seed=workloads.BASE_SEED, 
     for tv, h in zip(dw.tensors, host):
         if tv.scales is not None:
             w0 = workloads.initial_weights(wl, tv.tensor_id, device=DEV, base_seed=base_seed).cpu().numpy()
-            rc, rs = o32.quantize_rtn(oracle.FMT_E4M3 if tv.fmt == 0 else oracle.FMT_INT4, w0, wl.block_size,
+            rc, rs = o32.quantize_rtn(oracle.FMT_E4M3 if tv.fmt == 0 else oracle.FMT_INT4, w0, dw.group_size(tv),
                                       wl.scale_bf16)
             assert np.array_equal(h["codes"], rc) and np.array_equal(h["scales"].view(np.uint32), rs.view(np.uint32))
     worst = {}
@@ -108,7 +108,7 @@ def run_workload_parity(harness, o32, wl, steps, base_seed=workloads.BASE_SEED, 
         dw.plan.step(hp)
         torch.cuda.synchronize()
         for tv, h in zip(dw.tensors, host):
-            oracle_step(o32, h, tv.spec.numel, step_config(hp, tv.tensor_id, tv.fmt))
+            oracle_step(o32, h, tv.spec.numel, step_config(hp, tv.tensor_id, tv.fmt, group_size=dw.group_size(tv)))
             st = compare(host_copy(tv), h, f"{wl.name} step {k} tensor {tv.spec.name}", wl.state_bf16)
             for key, val in st.items():
                 worst[key] = max(worst.get(key, 0), val)
@@ -164,7 +164,7 @@ def _run_with_layout(harness, o32, wl, steps, over):
         dw.plan.step(hp)
         torch.cuda.synchronize()
         for tv, h in zip(dw.tensors, host):
-            oracle_step(o32, h, tv.spec.numel, step_config(hp, tv.tensor_id, tv.fmt))
+            oracle_step(o32, h, tv.spec.numel, step_config(hp, tv.tensor_id, tv.fmt, group_size=dw.group_size(tv)))
             st = compare(host_copy(tv), h, f"{wl.name} step {k} {tv.spec.name} {over}", wl.state_bf16)
             for key, val in st.items():
                 worst[key] = max(worst.get(key, 0), val)
@@ -215,6 +215,64 @@ def test_block_sizes(harness, o32, fmt, bs):
     wl = small_mixed_workload(fmt, block_size=bs)
     worst = _run_with_layout(harness, o32, wl, 3, {})
     assert worst["code_mismatch"] == 0, worst
+
+
+def wide_group_workload(fmt="fp8", **kw):
+    """Row-wise and tensor-wise scale groups (the paper's own granularities, Sec. 4.1 and 4.4) of many shapes:
+    rows from 8 to 8192 elements (1 to 16 waves per group), ragged last rows, one-scale tensors that fit one
+    workgroup and ones that need the two-pass kernels (with and without a ragged last tile)."""
+    T = workloads.TensorSpec
+    rows = [(5, 1152), (3, 6912), (2, 8192), (7, 520), (9, 96), (4, 1000), (33, 8), (6, 1024), (3, 4096), (2, 5000)]
+    ts = [T(f"row{i}", s, fmt, grad_std=1e-3 * (1 + i % 3), granularity="row") for i, s in enumerate(rows)]
+    ts.append(T("row_block_mix", (16, 256), fmt, granularity="row"))            # a row that is also a block size
+    ts += [T("tw_small", (4096,), fmt, granularity="tensor"), T("tw_8", (8,), fmt, granularity="tensor"),
+           T("tw_big", (300, 1024), fmt, granularity="tensor"), T("tw_ragged", (100003,), fmt, granularity="tensor"),
+           T("tw_odd_small", (1001,), fmt, granularity="tensor")]
+    ts.insert(4, T("blk", (3000,), fmt))                                          # ordinary block-128 tensor in the same plan
+    ts.insert(9, T("norm", (640,), "bf16_plain"))
+    return workloads.Workload("wide_" + fmt, ts, steps=3, **kw)
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
+@pytest.mark.parametrize("over", [dict(), dict(opt=1, round=1, lr=0.05), dict(mode=3), dict(opt=1, mode=2, lr=0.05),
+                                  dict(inject=False, weight_decay=0.1)])
+def test_row_wise_and_tensor_wise_groups(harness, o32, fmt, over):
+    worst = _run_with_layout(harness, o32, wide_group_workload(fmt), 3, over)
+    assert worst["code_mismatch"] == 0, worst
+
+
+def test_row_wise_bf16_state_and_scales(harness, o32):
+    worst = _run_with_layout(harness, o32, wide_group_workload("int4", state_bf16=True, scale_bf16=True, lr=1e-4), 3, {})
+    assert worst["code_mismatch"] == 0, worst
+
+
+def test_initial_quantization_of_wide_groups(harness, eco, o32):
+    wl = wide_group_workload("fp8")
+    dw = harness.DeviceWorkload(wl, DEV)
+    for tv in dw.tensors:
+        if tv.scales is None:
+            continue
+        w0 = workloads.initial_weights(wl, tv.tensor_id, device=DEV).cpu().numpy()
+        rc, rs = o32.quantize_rtn(FMT_E4M3, w0, dw.group_size(tv))
+        assert np.array_equal(tv.weights.cpu().numpy(), rc), tv.spec.name
+        assert np.array_equal(to_f32(tv.scales).view(np.uint32), rs.view(np.uint32)), tv.spec.name
+        out = torch.zeros(tv.spec.numel, device=DEV)
+        eco.eco_dequantize(tv.weights, tv.scales, tv.spec.numel, 0, dw.group_size(tv), 0, out)
+        ref = o32.dequantize(FMT_E4M3, rc, rs, tv.spec.numel, dw.group_size(tv))
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), tv.spec.name
+    dw.close()
+
+
+def test_unsupported_group_sizes_are_rejected(harness, eco):
+    n = 20000
+    z = torch.zeros(n, device=DEV)
+    c = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    g = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    for gs in (100, 12, 1004, 9000):
+        t = eco.make_tensor(c, z, g, z, z, n, 0, 0, group_size=gs)
+        with pytest.raises(eco.EcoError) as ei:
+            eco.eco_plan_create([t], eco.make_hparams())
+        assert ei.value.status == eco.ECO_EUNSUPPORTED, gs
 
 
 @pytest.mark.parametrize("fmt", ["fp8", "int4"])

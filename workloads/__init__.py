@@ -30,10 +30,19 @@ class TensorSpec:
     grad_std: float = 1e-3
     layer: int = -1             # layer index, -1 for embeddings
     expert: int = -1            # routed-expert index within the layer, -1 if not a routed expert
+    granularity: str = "block"  # scale groups: "block" (the workload's block size), "row" (last dimension), "tensor"
 
     @property
     def numel(self) -> int:
         return int(math.prod(self.shape))
+
+    def group_size(self, block_size: int) -> int:
+        """Elements per scale group of this tensor."""
+        if self.granularity == "row":
+            return int(self.shape[-1])
+        if self.granularity == "tensor":
+            return self.numel
+        return block_size
 
 
 @dataclass
@@ -137,6 +146,16 @@ def config5(layers: int = 28, vocab: int = 102400) -> Workload:
 
 
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
+
+
+def with_granularity(wl: Workload, granularity: str) -> Workload:
+    """The same parameter set with the paper's own scale granularities: "row" (row-wise FP8, Sec. 4.1) or
+    "tensor" (tensor-wise INT4, Sec. 4.4) on every quantized tensor."""
+    for t in wl.tensors:
+        if t.fmt in ("fp8", "int4"):
+            t.granularity = granularity
+    wl.name += "_" + granularity + "wise"
+    return wl
 
 
 def _mix(*xs: int) -> int:
