@@ -29,7 +29,9 @@ BYTES_PER_PARAM = {"fp8": 20.0625, "int4": 11.03125, "bf16_plain": 22.0}
 
 
 def algorithmic_bytes(wl, variant: str = "adam-sr") -> float:
-    """Bytes the method itself must move in one step (read + write), summed over the tensors."""
+    """Bytes the method itself must move in one step (read + write), summed over the tensors.  A tensor
+    with a single scale that does not fit one workgroup needs its inputs twice (the abs-max of theta~ must
+    be known before any element can be quantized): its reads count double."""
     adam = variant.startswith("adam")
     master = "master" in variant
     exact = "exact" in variant
@@ -40,10 +42,15 @@ def algorithmic_bytes(wl, variant: str = "adam-sr") -> float:
         if t.fmt in ("fp8", "int4"):
             code = 1.0 if t.fmt == "fp8" else 0.5
             sb = (2 if wl.scale_bf16 else 4) / wl.block_size
+            gs = t.group_size(wl.block_size)
+            sb = (2 if wl.scale_bf16 else 4) / gs
+            two_pass = gs >= t.numel and not (t.numel <= 8192 and t.numel % 8 == 0)
             if master:                                             # master read+write, codes and scales written only
-                per = 2 * 4 + code + sb + 2 + state
+                rd, wr = 4 + 2 + state / 2, 4 + code + sb + state / 2
             else:
-                per = 2 * code + 2 * sb + 2 + state + (2 * 4 if exact else 0)
+                rd = code + sb + 2 + state / 2 + (4 if exact else 0)
+                wr = code + sb + state / 2 + (4 if exact else 0)
+            per = rd * (2 if two_pass else 1) + wr
         else:
             per = 2 * 2 + 2 + state
         total += t.numel * per
@@ -138,6 +145,9 @@ def main() -> int:
                     help="optimizer / mode / rounding variant of the step (the headline metric is adam-sr = Adam-ECO "
                          "with stochastic rounding; 'master' is the fp32-master-weight baseline, 'exact' the "
                          "stored-error injection of Appendix A, 'naive' master weights removed without injection)")
+    ap.add_argument("--granularity", default="block", choices=["block", "row", "tensor"],
+                    help="scale groups of the quantized tensors: the configuration's 128-element blocks (headline), "
+                         "one scale per row (the paper's FP8 runs) or per tensor (its INT4 run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
@@ -167,6 +177,8 @@ def main() -> int:
         eco.eco_set_option(1, args.lds_bytes)
 
     wl = workloads.CONFIGS[args.config]()
+    if args.granularity != "block":
+        wl = workloads.with_granularity(wl, args.granularity)
     over = {}
     if args.variant.startswith("sgdm"):
         over["opt"] = eco.ECO_OPT_SGDM
@@ -216,13 +228,13 @@ def main() -> int:
         "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "tensors": len(wl.tensors), "parameters": wl.numel,
+        "config": {"workload": wl.name, "granularity": args.granularity, "tensors": len(wl.tensors), "parameters": wl.numel,
                    "format": "fp8_e4m3 codes, block-128 fp32 scales, bf16 gradients, fp32 m and v"
                    if args.config != 5 else "int4 codes, group-128 bf16 scales, bf16 gradients, bf16 m and v",
                    "optimizer": args.variant, "launches_per_step": 1 if args.config != 2 else 2},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": profiled_traffic(wl.name) if args.variant == "adam-sr" else None,
+                     "traffic": profiled_traffic(wl.name) if args.variant == "adam-sr" and args.granularity == "block" else None,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": avg_kernel_s * 1e3},
     }
     dw.close()

@@ -421,8 +421,12 @@ __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
   const uint64_t start = grp * td.group_size;
   const uint64_t end = start + td.group_size < td.numel ? start + td.group_size : td.numel;
   const uint64_t e0 = start + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-  step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_LANE, RED_WG>(a, td, e0, valid_from(e0, end), grp,
-                                                                        threadIdx.x == 0, nullptr);
+  // a group that fills every lane of the workgroup (e.g. rows of 1024, 2048, 4096) needs no per-lane guards
+  if (end - start == (uint64_t)blockDim.x * ELEMS_PER_LANE)
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED_WG>(a, td, e0, 8, grp, threadIdx.x == 0, nullptr);
+  else
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_LANE, RED_WG>(a, td, e0, valid_from(e0, end), grp,
+                                                                          threadIdx.x == 0, nullptr);
 }
 
 // (4) One scale per tensor (tensor-wise scaling, Sec. 4.4), tensors too large for one workgroup: two passes
@@ -432,9 +436,13 @@ __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, int RED>
 __global__ __launch_bounds__(WG_THREADS) void eco_step_tensorwise_kernel(const StepArgs a) {
   const TensorDesc td = load_tensor_desc(a, load_table(a.tw_tile_tensor, blockIdx.x));
-  const uint64_t e0 = (uint64_t)(blockIdx.x - td.first_unit) * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-  step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_LANE, RED>(a, td, e0, valid_from(e0, td.numel), 0, false,
-                                                                     a.slots + td.slot);
+  const uint64_t tile_off = (uint64_t)(blockIdx.x - td.first_unit) * TILE_ELEMS;
+  const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  if (tile_off + TILE_ELEMS <= td.numel)
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED>(a, td, e0, 8, 0, false, a.slots + td.slot);
+  else
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_GUARDED, RED>(a, td, e0, valid_from(e0, td.numel), 0, false,
+                                                                          a.slots + td.slot);
 }
 
 template <int FMT, bool SCALE_BF16>
