@@ -229,9 +229,12 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "granularity": args.granularity, "tensors": len(wl.tensors), "parameters": wl.numel,
-                   "format": "fp8_e4m3 codes, block-128 fp32 scales, bf16 gradients, fp32 m and v"
-                   if args.config != 5 else "int4 codes, group-128 bf16 scales, bf16 gradients, bf16 m and v",
-                   "optimizer": args.variant, "launches_per_step": 1 if args.config != 2 else 2},
+                   "format": ("fp8_e4m3 codes, %s fp32 scales, bf16 gradients, fp32 m and v"
+                              if args.config != 5 else "int4 codes, %s bf16 scales, bf16 gradients, bf16 m and v")
+                   % {"block": "block-128", "row": "row-wise", "tensor": "tensor-wise"}[args.granularity],
+                   "optimizer": args.variant,
+                   "launches_per_step": {"block": 1 if args.config != 2 else 2, "row": "one per row length",
+                                         "tensor": "two passes, a reduction and a scale kernel"}[args.granularity]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": profiled_traffic(wl.name) if args.variant == "adam-sr" and args.granularity == "block" else None,

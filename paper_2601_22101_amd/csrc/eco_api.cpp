@@ -104,6 +104,7 @@ struct Group {                           // the tensors of one storage format
   std::vector<uint32_t> tw_tensor;       // tensor-wise: the tensors
   eco::TensorDesc *d_descs = nullptr;
   uint32_t *d_tables = nullptr;          // all the lists above, back to back, then the abs-max slots
+  uint32_t *d_tile_max = nullptr;        // scratch of the tensor-wise passes: one entry per tensor-wise tile
   size_t off_ragged = 0, off_wide[eco::MAX_WIDE_WAVES + 1] = {0}, off_tw_tiles = 0, off_tw_tensor = 0, off_slots = 0;
 };
 
@@ -205,6 +206,7 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan) {
   for (Group &g : plan->groups) {
     if (g.d_descs) (void)hipFree(g.d_descs);
     if (g.d_tables) (void)hipFree(g.d_tables);
+    if (g.d_tile_max) (void)hipFree(g.d_tile_max);
   }
   delete plan;
   return st;
@@ -315,6 +317,8 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
     }
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&g.d_descs), g.descs.size() * sizeof(eco::TensorDesc));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&g.d_tables), host.size() * sizeof(uint32_t));
+    if (e == hipSuccess && !g.tw_tile_tensor.empty())
+      e = hipMalloc(reinterpret_cast<void **>(&g.d_tile_max), g.tw_tile_tensor.size() * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemcpy(g.d_descs, g.descs.data(), g.descs.size() * sizeof(eco::TensorDesc), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(g.d_tables, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
@@ -356,6 +360,7 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     a.tw_tile_tensor = g.d_tables + g.off_tw_tiles;
     a.tw_tensor = g.d_tables + g.off_tw_tensor;
     a.slots = g.d_tables + g.off_slots;
+    a.tile_max = g.d_tile_max;
     a.num_tw_tiles = static_cast<uint32_t>(g.tw_tile_tensor.size());
     a.num_tw_tensors = static_cast<uint32_t>(g.tw_tensor.size());
     a.b1 = c.b1; a.omb1 = c.omb1; a.b2 = c.b2; a.omb2 = c.omb2; a.rbc2 = c.rbc2; a.c1 = c.c1; a.eps = c.eps;

@@ -25,6 +25,16 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Two fp32 -> one dword of two bfloat16 (lo in the low half), round to nearest even.  The vector
+// conversion compiles to gfx950's packed conversion instruction, whose result equals
+// f32_to_bf16_rne() for every finite fp32 input (compared exhaustively on the device).
+typedef __bf16 eco_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float eco_f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_rne(float lo, float hi) {
+  const eco_f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, eco_bf16x2_t));
+}
+
 // ---------------------------------------------------------------------------------- E4M3 (OCP)
 // Decode byte SEL of a dword holding four codes.  gfx950's fp8 conversion instructions implement
 // the OCP E4M3 encoding (bias 7, subnormals, S.1111.111 = NaN), and a decode is exact, so the

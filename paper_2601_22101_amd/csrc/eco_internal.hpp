@@ -57,7 +57,8 @@ struct StepArgs {            // by-value kernel argument: everything wave-unifor
   const uint32_t *wide_tensor;     // wide groups of the launch in flight: group -> index into tensors
   const uint32_t *tw_tile_tensor;  // tensor-wise scaling: tile (full or partial) -> index into tensors
   const uint32_t *tw_tensor;       //   ... the tensors themselves
-  uint32_t *slots;                 //   ... one abs-max slot (fp32 bit pattern) per such tensor, zero between steps
+  uint32_t *slots;                 //   ... one abs-max slot (fp32 bit pattern) per such tensor
+  uint32_t *tile_max;              //   ... scratch: the abs-max of every such tile, written and consumed within a step
   uint32_t num_tiles, num_ragged, num_tw_tiles, num_tw_tensors;
   float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd, inv_lr, inv_lr_beta;
   uint32_t seed_lo, seed_hi, step_lo;

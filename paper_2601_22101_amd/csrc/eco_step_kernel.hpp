@@ -84,16 +84,15 @@ __device__ __forceinline__ void store_f32x8(float *p, int nvalid, const float (&
 
 template <int ACC>
 __device__ __forceinline__ void store_bf16x8(uint16_t *p, int nvalid, const float (&x)[8]) {
-  uint32_t h[8];
+  uint32_t h[4];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) h[j] = f32_to_bf16_rne(x[j]);
+  for (int j = 0; j < 4; ++j) h[j] = f32x2_to_bf16x2_rne(x[2 * j], x[2 * j + 1]);
   if (use_vector<ACC>(nvalid)) {
-    *reinterpret_cast<uint4 *>(p) =
-        make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    *reinterpret_cast<uint4 *>(p) = make_uint4(h[0], h[1], h[2], h[3]);
   } else {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      if (j < nvalid) p[j] = (uint16_t)h[j];
+      if (j < nvalid) p[j] = (uint16_t)(h[j >> 1] >> (16 * (j & 1)));
   }
 }
 
@@ -225,11 +224,14 @@ __device__ __forceinline__ void sqrt_plus_eps8(const float (&x)[8], float eps, f
 // How the abs-max of a scale group is obtained:
 //   RED_BLOCK  the group is 2^shift elements inside one wave: DPP/swizzle all-reduce over its lanes
 //   RED_WG     the group is the whole workgroup (1..16 waves): wave all-reduce, then an LDS combine
-//   RED_ATOMIC first pass of a group larger than a workgroup (tensor-wise scaling): wave all-reduce, one
-//              atomic max per wave into the group's slot of the plan's scratch; nothing else is written
+//   RED_ATOMIC first pass of a group larger than a workgroup, one group at a time (the initial quantizer):
+//              wave all-reduce, one atomic max per wave into the group's slot; nothing else is written
+//   RED_TILE   first pass of the step for such groups (tensor-wise scaling): wave all-reduce, the wave's
+//              maximum goes to its tile's entry of a scratch array, which a small kernel folds into the
+//              tensor's slot (tens of thousands of atomics on one address serialize in the memory system)
 //   RED_SLOT   second pass: the abs-max is read from that slot; everything is recomputed and written
-//              except the scale (a third, tiny kernel writes it once every tile has used the old one)
-enum : int { RED_BLOCK = 0, RED_WG = 1, RED_ATOMIC = 2, RED_SLOT = 3 };
+//              except the scale (a last, tiny kernel writes it once every tile has used the old one)
+enum : int { RED_BLOCK = 0, RED_WG = 1, RED_ATOMIC = 2, RED_SLOT = 3, RED_TILE = 4 };
 
 template <int RED>
 __device__ __forceinline__ float group_absmax(float lane_max, int shift, uint32_t *slot) {
@@ -237,7 +239,14 @@ __device__ __forceinline__ float group_absmax(float lane_max, int shift, uint32_
   if (RED == RED_SLOT) return u2f(*slot);
   const uint32_t wmax = group_umax(f2u(lane_max), 64);
   if (RED == RED_ATOMIC) {
-    if ((threadIdx.x & 63) == 0) atomicMax(slot, wmax);
+    // the slot only grows, so a wave whose maximum does not exceed what the slot already holds has
+    // nothing to add; the read goes to the device-coherent cache level, and the atomic is what decides
+    if ((threadIdx.x & 63) == 0 && wmax > __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+      atomicMax(slot, wmax);
+    return 0.0f;
+  }
+  if (RED == RED_TILE) {
+    if ((threadIdx.x & 63) == 0) *slot = wmax;
     return 0.0f;
   }
   // RED_WG
@@ -258,7 +267,7 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
                                           uint64_t sg, bool scale_writer, uint32_t *slot) {
   constexpr bool ADAM = algo_is_adam(ALGO);
   constexpr bool MASTER = algo_is_master(ALGO);
-  constexpr bool WRITE = RED != RED_ATOMIC;       // the first pass of a two-pass group writes nothing
+  constexpr bool WRITE = RED != RED_ATOMIC && RED != RED_TILE;   // the first pass of a two-pass group writes nothing
   const bool any = ACC == ACC_FULL || nvalid > 0;
 
   float g[8], m[8], v[8], w[8];
@@ -430,19 +439,38 @@ __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
 }
 
 // (4) One scale per tensor (tensor-wise scaling, Sec. 4.4), tensors too large for one workgroup: two passes
-// over 512-element tiles.  Pass 1 recomputes theta~ and folds its abs-max into the tensor's slot; pass 2
-// recomputes theta~ again (the inputs are untouched so far), quantizes against the slot's value and writes
-// codes and state; a last kernel writes the new scales and clears the slots.
+// over 512-element tiles.  Pass 1 recomputes theta~ and leaves each tile's abs-max in a scratch array, which
+// a reduction kernel (one workgroup per tensor) folds into the tensor's slot; pass 2 recomputes theta~ again
+// (the inputs are untouched so far), quantizes against the slot's value and writes codes and state; a last
+// kernel writes the new scales.
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, int RED>
 __global__ __launch_bounds__(WG_THREADS) void eco_step_tensorwise_kernel(const StepArgs a) {
   const TensorDesc td = load_tensor_desc(a, load_table(a.tw_tile_tensor, blockIdx.x));
   const uint64_t tile_off = (uint64_t)(blockIdx.x - td.first_unit) * TILE_ELEMS;
   const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
+  uint32_t *slot = RED == RED_TILE ? a.tile_max + blockIdx.x : a.slots + td.slot;
   if (tile_off + TILE_ELEMS <= td.numel)
-    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED>(a, td, e0, 8, 0, false, a.slots + td.slot);
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED>(a, td, e0, 8, 0, false, slot);
   else
-    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_GUARDED, RED>(a, td, e0, valid_from(e0, td.numel), 0, false,
-                                                                          a.slots + td.slot);
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_GUARDED, RED>(a, td, e0, valid_from(e0, td.numel), 0, false, slot);
+}
+
+constexpr int TW_REDUCE_THREADS = 1024;
+template <int FMT>   // a template only so that every translation unit may hold its own copy
+__global__ __launch_bounds__(TW_REDUCE_THREADS) void eco_tensorwise_reduce_kernel(const StepArgs a) {
+  const TensorDesc td = load_tensor_desc(a, a.tw_tensor[blockIdx.x]);
+  const uint64_t ntiles = (td.numel + TILE_ELEMS - 1) / TILE_ELEMS;
+  const uint32_t *tm = a.tile_max + td.first_unit;
+  uint32_t r = 0;
+  for (uint64_t i = threadIdx.x; i < ntiles; i += TW_REDUCE_THREADS) { const uint32_t x = tm[i]; r = r > x ? r : x; }
+  r = group_umax(r, 64);
+  __shared__ uint32_t wave_max[TW_REDUCE_THREADS / 64];
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = r;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int k = 1; k < TW_REDUCE_THREADS / 64; ++k) { const uint32_t o = wave_max[k]; r = r > o ? r : o; }
+    a.slots[td.slot] = r;
+  }
 }
 
 template <int FMT, bool SCALE_BF16>
@@ -454,7 +482,6 @@ __global__ __launch_bounds__(WG_THREADS) void eco_tensorwise_scale_kernel(const 
   block_scale<FMT, SCALE_BF16>(u2f(a.slots[td.slot]), s_new, inv);
   if (SCALE_BF16) static_cast<uint16_t *>(td.s)[0] = (uint16_t)(f2u(s_new) >> 16);
   else static_cast<float *>(td.s)[0] = s_new;
-  a.slots[td.slot] = 0;
 }
 
 template <int FMT, bool STATE_BF16, bool SC, int RD>
@@ -475,8 +502,10 @@ void launch_step_algos(const KernelVariant &kv, const StepArgs &args, unsigned g
                          dim3(64 * nw), 0, stream, wa);                                                           \
     }                                                                                                             \
     if (args.num_tw_tiles) {                                                                                      \
-      hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_ATOMIC>),                   \
+      hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_TILE>),                     \
                          dim3(args.num_tw_tiles), dim3(WG_THREADS), 0, stream, args);                             \
+      hipLaunchKernelGGL((eco_tensorwise_reduce_kernel<FMT>), dim3(args.num_tw_tensors), dim3(TW_REDUCE_THREADS), \
+                         0, stream, args);                                                                        \
       hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_SLOT>),                     \
                          dim3(args.num_tw_tiles), dim3(WG_THREADS), 0, stream, args);                             \
       hipLaunchKernelGGL((eco_tensorwise_scale_kernel<FMT, SC>),                                                  \
