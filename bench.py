@@ -152,6 +152,9 @@ def main() -> int:
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
                          "per tensor (same distribution; for runs under rocprofv3 --pmc)")
+    ap.add_argument("--bulk-init", action="store_true",
+                    help="write the initial quantized weights with a few launches over the whole arenas (arbitrary valid "
+                         "codes and scales instead of quantized N(0, 0.02) draws; for runs under rocprofv3 --pmc)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed steps, run two plain 1 GiB device copies (a reference of known size for "
                          "scaling rocprofv3 byte counters)")
@@ -191,7 +194,7 @@ def main() -> int:
     elif "naive" in args.variant:
         over["mode"] = eco.ECO_MODE_NAIVE
     t_setup = time.perf_counter()
-    dw = harness.DeviceWorkload(wl, "cuda:0", layout=over)
+    dw = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk" if args.bulk_init else True)
     torch.cuda.synchronize()
     print(f"[bench] {wl.name}: {len(wl.tensors)} tensors, {wl.numel} parameters, set-up {time.perf_counter() - t_setup:.1f} s",
           file=sys.stderr, flush=True)

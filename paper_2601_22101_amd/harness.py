@@ -42,7 +42,7 @@ class DeviceWorkload:
     has its own descriptor in the plan and its own, 256-byte aligned, slices."""
 
     def __init__(self, wl: Workload, device: str = "cuda:0", base_seed: int = workloads.BASE_SEED,
-                 init: bool = True, layout: Optional[dict] = None):
+                 init=True, layout: Optional[dict] = None):
         """`layout`: hyper-parameter overrides that are fixed for the life of the plan (opt, mode, ...).
         In the master-weight mode the fp32 initial weights are kept as the master copy; in the
         exact-injection mode the aux buffer starts as e_0 = theta_0 - q(theta_0) (Appendix A)."""
@@ -102,7 +102,9 @@ class DeviceWorkload:
             o = offs[i]
             self.tensors.append(TensorViews(t, i, _FMT[t.fmt], w, s, self.grad[o:o + n], self.m[o:o + n],
                                             self.v[o:o + n], None if self.aux is None else self.aux[o:o + n]))
-        if init:
+        if init == "bulk":
+            self.init_weights_bulk()
+        elif init:
             self.init_weights()
         self.plan = eco.Plan([self.descriptor(tv) for tv in self.tensors], self.hparams(1))
 
@@ -145,6 +147,31 @@ class DeviceWorkload:
             else:
                 tv.weights.copy_(w.to(torch.bfloat16))
             del w
+        torch.cuda.synchronize(self.device)
+
+    def init_weights_bulk(self) -> None:
+        """Valid but arbitrary quantized weights written with a handful of launches over the whole arenas
+        (random non-NaN codes, one constant scale; other values than init_weights, same shapes and bytes):
+        for runs under a counter-collecting profiler, where every launch is expensive.  Quantized,
+        non-master layouts only."""
+        assert self.mode in (eco.ECO_MODE_ECO, eco.ECO_MODE_NAIVE)
+        g = torch.Generator(device=self.device)
+        g.manual_seed(workloads._mix(self.base_seed, 0x77, 0))
+        chunk = 1 << 30
+        for o in range(0, self.codes.numel(), chunk):
+            n = min(chunk, self.codes.numel() - o)
+            if all(tv.fmt == eco.ECO_FMT_FP8_E4M3 for tv in self.tensors if tv.scales is not None):
+                # magnitude codes 0x00..0x77 (up to 240), random sign bit: never the NaN patterns 0x7F / 0xFF
+                x = torch.randint(0, 0x78, (n,), generator=g, device=self.device, dtype=torch.uint8)
+                x |= torch.randint(0, 2, (n,), generator=g, device=self.device, dtype=torch.uint8) << 7
+            else:
+                # two nibbles in [-7, 7]: never the unused code -8
+                lo = torch.randint(-7, 8, (n,), generator=g, device=self.device, dtype=torch.int16)
+                hi = torch.randint(-7, 8, (n,), generator=g, device=self.device, dtype=torch.int16)
+                x = ((lo & 0xF) | ((hi & 0xF) << 4)).to(torch.uint8)
+            self.codes[o:o + n].copy_(x)
+            del x
+        self.scales.fill_(0.02 * 4 / 448 if self.scales.dtype == torch.float32 else 2.0 ** -9)
         torch.cuda.synchronize(self.device)
 
     def fill_gradients(self, step: int) -> None:
