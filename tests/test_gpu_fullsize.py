@@ -20,65 +20,73 @@ SPAN_BLOCKS = 48          # 6144 elements: twelve 512-element tiles, not tile al
 
 
 def pick_spans(wl, rng, n_tensors):
+    """(tensor, first group, number of groups) samples; groups are the tensor's own scale groups (blocks,
+    rows, or the whole tensor), spans hold about SPAN_BLOCKS * 128 elements."""
     ids = {0, len(wl.tensors) - 1}
     ids |= {i for i, t in enumerate(wl.tensors) if "router" in t.name or "embed" in t.name and t.fmt != "bf16_plain"}
     ids = set(sorted(ids)[:6]) | {len(wl.tensors) - 1}
     quant = [i for i, t in enumerate(wl.tensors) if t.fmt in ("fp8", "int4")]
     ids |= set(int(x) for x in rng.choice(quant, size=min(n_tensors, len(quant)), replace=False))
     spans = []
-    bs = wl.block_size
     for i in sorted(ids):
         t = wl.tensors[i]
         if t.fmt not in ("fp8", "int4"):
             continue
-        nb = (t.numel + bs - 1) // bs
-        starts = {0, max(0, nb - SPAN_BLOCKS)}
-        if nb > 2 * SPAN_BLOCKS:
-            starts.add(int(rng.integers(1, nb - SPAN_BLOCKS)))
-        for b0 in sorted(starts):
-            n = min(SPAN_BLOCKS, nb - b0)
-            spans.append((i, b0, n))
+        gs = t.group_size(wl.block_size)
+        ng = (t.numel + gs - 1) // gs
+        per = max(1, SPAN_BLOCKS * 128 // gs)
+        starts = {0, max(0, ng - per)}
+        if ng > 2 * per:
+            starts.add(int(rng.integers(1, ng - per)))
+        for g0 in sorted(starts):
+            spans.append((i, g0, min(per, ng - g0)))
     return spans
 
 
-def grab(tv, wl, b0, nblocks):
-    """Host copy of blocks [b0, b0+nblocks) of one tensor."""
-    bs = wl.block_size
-    e0, e1 = b0 * bs, min((b0 + nblocks) * bs, tv.spec.numel)
+def grab(tv, wl, g0, ngroups, with_aux=False):
+    """Host copy of scale groups [g0, g0+ngroups) of one tensor."""
+    gs = tv.spec.group_size(wl.block_size)
+    e0, e1 = g0 * gs, min((g0 + ngroups) * gs, tv.spec.numel)
+    assert e0 % 2 == 0
     if tv.fmt == 0:
         codes = tv.weights[e0:e1]
     else:
         codes = tv.weights[e0 // 2:(e1 + 1) // 2]
-    return dict(codes=codes.cpu().numpy().copy(), scales=to_f32(tv.scales[b0:b0 + nblocks]),
-                grad=bf16_bits(tv.grad[e0:e1]), m=to_f32(tv.m[e0:e1]), v=to_f32(tv.v[e0:e1])), e1 - e0
+    h = dict(codes=codes.cpu().numpy().copy(), scales=to_f32(tv.scales[g0:g0 + ngroups]),
+             grad=bf16_bits(tv.grad[e0:e1]), m=to_f32(tv.m[e0:e1]), v=to_f32(tv.v[e0:e1]))
+    if with_aux:
+        h["aux"] = to_f32(tv.aux[e0:e1])
+    return h, e1 - e0
 
 
-def run_fullsize(wl, steps, n_tensors, seed):
+def run_fullsize(wl, steps, n_tensors, seed, layout=None):
     from paper_2601_22101_amd import harness
     o32 = oracle.get("f32")
     rng = np.random.default_rng(seed)
-    dw = harness.DeviceWorkload(wl, DEV)
+    dw = harness.DeviceWorkload(wl, DEV, layout=layout)
+    with_aux = dw.aux is not None
     total_checked = 0
     mism = 0
     for k in range(1, steps + 1):
         dw.fill_gradients(k)
         spans = pick_spans(wl, rng, n_tensors)
-        before = [grab(dw.tensors[i], wl, b0, n) for i, b0, n in spans]
+        before = [grab(dw.tensors[i], wl, g0, n, with_aux) for i, g0, n in spans]
         hp = dw.hparams(k)
         dw.plan.step(hp)
         torch.cuda.synchronize()
-        for (i, b0, n), (h, numel) in zip(spans, before):
+        for (i, g0, n), (h, numel) in zip(spans, before):
             tv = dw.tensors[i]
-            oracle_step(o32, h, numel, step_config(hp, tv.tensor_id, tv.fmt, elem_offset=b0 * wl.block_size))  # block-128 workloads
-            after, _ = grab(tv, wl, b0, n)
+            gs = tv.spec.group_size(wl.block_size)
+            oracle_step(o32, h, numel, step_config(hp, tv.tensor_id, tv.fmt, elem_offset=g0 * gs, group_size=gs))
+            after, _ = grab(tv, wl, g0, n, with_aux)
             after["grad"] = h["grad"]
-            st = compare(after, h, f"{wl.name} step {k} {tv.spec.name} blocks {b0}+{n}", wl.state_bf16)
+            st = compare(after, h, f"{wl.name} step {k} {tv.spec.name} groups {g0}+{n}", wl.state_bf16)
             mism += st["code_mismatch"]
             total_checked += numel
         # whole-arena properties: every stored value finite, v non-negative, inactive experts still moved
         assert torch.isfinite(dw.m.float().sum()) and torch.isfinite(dw.v.float().sum())
         assert float(dw.v.min()) >= 0.0
-    if wl.n_inactive:
+    if wl.n_inactive and dw.hparams(1).opt == 0:
         # an expert that never received a gradient keeps m = v = 0 only if it was inactive at every step;
         # one that was inactive at the last step but active before must still have had its state stepped
         last = steps
@@ -108,3 +116,32 @@ def test_config4_smoe_shaped_sampled():
 def test_config5_deepseek_shaped_int4_sampled():
     n = run_fullsize(workloads.config5(), steps=3, n_tensors=24, seed=5)
     assert n > 1_000_000
+
+
+def test_config4_row_wise_sampled():
+    """One scale per row (Sec. 4.1): the wide-group kernel at full size; spans are whole rows."""
+    n = run_fullsize(workloads.with_granularity(workloads.config4(), "row"), steps=3, n_tensors=16, seed=14)
+    assert n > 300_000
+
+
+def test_config4_tensor_wise_sampled():
+    """One scale per tensor (Sec. 4.4): the two-pass kernels at full size; every sampled tensor is recomputed whole
+    (the embedding of 51.5 M elements and the 65 536-element router included)."""
+    n = run_fullsize(workloads.with_granularity(workloads.config4(), "tensor"), steps=2, n_tensors=6, seed=15)
+    assert n > 50_000_000
+
+
+def test_config5_tensor_wise_int4_sampled():
+    """The paper's INT4 setting (tensor-wise scales) on the DeepSeek-shaped set with bf16 state and scales."""
+    n = run_fullsize(workloads.with_granularity(workloads.config5(), "tensor"), steps=2, n_tensors=4, seed=16)
+    assert n > 100_000_000
+
+
+@pytest.mark.parametrize("variant", ["adam-master", "sgdm-eco", "sgdm-exact"])
+def test_config4_other_modes_sampled(variant):
+    from paper_2601_22101_amd import binding as eco
+    layout = {"adam-master": dict(mode=eco.ECO_MODE_MASTER),
+              "sgdm-eco": dict(opt=eco.ECO_OPT_SGDM),
+              "sgdm-exact": dict(opt=eco.ECO_OPT_SGDM, mode=eco.ECO_MODE_EXACT)}[variant]
+    n = run_fullsize(workloads.config4(), steps=2, n_tensors=12, seed=17, layout=layout)
+    assert n > 300_000
