@@ -143,7 +143,9 @@ typedef struct eco_plan eco_plan_t;
  *                memory layout the descriptors are checked against)
  *   out        : receives the plan; owned by the library until eco_plan_destroy
  * Allocates device memory for the tables (80 bytes per tensor + 4 bytes per 512 elements, or per scale group
- * for groups wider than 512) and copies them synchronously.  Errors: ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_ENOMEM, ECO_EHIP.
+ * for groups wider than 512; for tensors with a single scale over more than 8192 elements another 4 bytes per
+ * 512 elements of scratch) and copies them synchronously.
+ * Errors: ECO_EINVAL, ECO_EALIGN, ECO_EUNSUPPORTED, ECO_ENOMEM, ECO_EHIP.
  */
 eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *layout, eco_plan_t **out);
 
@@ -154,7 +156,8 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan);
  * eco_step — one ECO step (Alg. 1 with Alg. 3 or Alg. 2) over every tensor of the plan.
  * Asynchronous on `stream`; allocates nothing.  Launches per storage format present: one kernel over the full
  * 512-element tiles of block-scaled tensors, one over their ragged tails if any, one per workgroup size for wide
- * groups, and three for tensors with a single scale (abs-max pass, apply pass, scale write).
+ * groups, and four for tensors with a single scale (abs-max pass into the plan's scratch, its reduction, apply
+ * pass, scale write).  Steps of one plan that use that scratch must not overlap each other on different streams.
  * hp->block_size, state_dtype, scale_dtype, opt and mode must equal the plan's.
  */
 eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream);
