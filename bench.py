@@ -5,8 +5,9 @@
 
 A "step" is one eco_step call over the whole synthetic parameter set (dequantize, Adam update without
 master weights, abs-max re-quantization with stochastic rounding, error injection into momentum), with
-all inputs resident in HBM.  Fresh bf16 gradients are drawn on the device before every step, outside
-the timed region.  Prints ONE JSON line.
+all inputs resident in HBM.  The fresh bf16 gradients of every step are drawn on the device before the
+timed region, one gradient arena per step; the K timed steps then run back to back between two
+synchronizations.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -155,6 +156,10 @@ def main() -> int:
     ap.add_argument("--granularity", default="block", choices=["block", "row", "tensor"],
                     help="scale groups of the quantized tensors: the configuration's 128-element blocks (headline), "
                          "one scale per row (the paper's FP8 runs) or per tensor (its INT4 run)")
+    ap.add_argument("--placement", default="auto", choices=["auto", "packed", "spread"],
+                    help="where the harness puts the arenas in HBM: one allocation per arena (packed), or one allocation "
+                         "with the codes+gradient, m and v arenas tens of GiB apart (spread; auto = spread for workloads "
+                         "of 8 GiB and more): arrays streamed in lock-step are faster from different regions of HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
@@ -200,34 +205,44 @@ def main() -> int:
         over["mode"] = eco.ECO_MODE_EXACT
     elif "naive" in args.variant:
         over["mode"] = eco.ECO_MODE_NAIVE
+    # One gradient arena (and one plan over the same weights and state) per step, as far as memory allows, so that
+    # every step's fresh gradients are resident before the timed region and the K steps run back to back in it.
+    total_steps = args.warmup + args.steps
+    free = torch.cuda.mem_get_info()[0]
+    base_need = harness.DeviceWorkload.pool_bytes(wl, over.get("mode", eco.ECO_MODE_ECO))
+    per_set = 2 * wl.numel + (4 << 20)
+    grad_sets = int(max(1, min(total_steps, (0.45 * free - base_need) // per_set + 1)))
     t_setup = time.perf_counter()
-    dw = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk" if args.bulk_init else True)
-    torch.cuda.synchronize()
-    print(f"[bench] {wl.name}: {len(wl.tensors)} tensors, {wl.numel} parameters, set-up {time.perf_counter() - t_setup:.1f} s",
-          file=sys.stderr, flush=True)
-
+    dw = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk" if args.bulk_init else True,
+                                placement=args.placement, grad_sets=grad_sets)
     fill = dw.fill_gradients_bulk if args.bulk_grad else dw.fill_gradients
+    for g in range(grad_sets):
+        fill(g + 1, g)                            # step k reads set (k - 1) mod grad_sets
+    torch.cuda.synchronize()
+    print(f"[bench] {wl.name}: {len(wl.tensors)} tensors, {wl.numel} parameters, {grad_sets} gradient sets, "
+          f"placement: {dw.placement}, set-up {time.perf_counter() - t_setup:.1f} s", file=sys.stderr, flush=True)
+
     k = 0
     for _ in range(args.warmup):
         k += 1
-        fill(k)
-        dw.step(k)
+        dw.step(k, (k - 1) % grad_sets)
     torch.cuda.synchronize()
 
-    wall, kernel_ms = 0.0, []
-    for _ in range(args.steps):
+    # the timed region: exactly K steps, nothing else on the device, one synchronize on each side
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    first = k + 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
         k += 1
-        fill(k)                                   # fresh gradients, outside the timed region
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record()
-        dw.step(k)
-        e1.record()
-        torch.cuda.synchronize()
-        wall += time.perf_counter() - t0
-        kernel_ms.append(e0.elapsed_time(e1))
-        print(f"[bench] step {k}: {kernel_ms[-1]:.3f} ms", file=sys.stderr, flush=True)
+        events[i].record()
+        dw.step(k, (k - 1) % grad_sets)
+    events[args.steps].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [events[i].elapsed_time(events[i + 1]) for i in range(args.steps)]
+    for i, ms in enumerate(kernel_ms):
+        print(f"[bench] step {first + i}: {ms:.3f} ms", file=sys.stderr, flush=True)
 
     ms_per_step = wall / args.steps * 1e3
     value = wl.numel / (ms_per_step * 1e-3)
@@ -237,8 +252,10 @@ def main() -> int:
     out = {
         "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32",
+        "data": "synthetic" if grad_sets >= total_steps else f"synthetic ({grad_sets} gradient sets reused in turn)",
         "config": {"workload": wl.name, "granularity": args.granularity, "tensors": len(wl.tensors), "parameters": wl.numel,
+                   "placement": dw.placement,
                    "format": ("fp8_e4m3 codes, %s fp32 scales, bf16 gradients, fp32 m and v"
                               if args.config != 5 else "int4 codes, %s bf16 scales, bf16 gradients, bf16 m and v")
                    % {"block": "block-128", "row": "row-wise", "tensor": "tensor-wise"}[args.granularity],

@@ -123,10 +123,11 @@ uint32_t default_lds_bytes(const eco::KernelVariant &kv) {
   if (kv.state_bf16 || kv.fmt == eco::FMT_BF16_PLAIN || kv.fmt == eco::FMT_FP32_ID) return 0;
   int waves;
   switch (kv.algo) {
-    case eco::ALGO_ADAM: waves = 12; break;          // 20.1 B/parameter
+    case eco::ALGO_ADAM: waves = 11; break;          // 20.1 B/parameter
     case eco::ALGO_ADAM_MASTER: waves = 8; break;    // 27.0
-    case eco::ALGO_SGDM: waves = 16; break;          // 12.1
-    default: waves = 12; break;                      // SGDM with master weights or stored error: 19-20
+    case eco::ALGO_SGDM: waves = 14; break;          // 12.1
+    case eco::ALGO_SGDM_MASTER: waves = 10; break;   // 19.0
+    default: waves = 11; break;                      // SGDM with a stored error: 20.1
   }
   return static_cast<uint32_t>(163840 / waves / 512 * 512);
 }
