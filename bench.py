@@ -143,7 +143,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload number (1-5) of the baseline's configs")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning: workgroups per compute unit (0 = default)")
     ap.add_argument("--lds-bytes", type=int, default=-1, help="launch tuning: dynamic LDS per workgroup (-1 = default)")
@@ -160,6 +160,7 @@ def main() -> int:
                     help="where the harness puts the arenas in HBM: one allocation per arena (packed), or one allocation "
                          "with the codes+gradient, m and v arenas tens of GiB apart (spread; auto = spread for workloads "
                          "of 8 GiB and more): arrays streamed in lock-step are faster from different regions of HBM")
+    ap.add_argument("--spread-gap-gib", type=int, default=0, help="distance between the arena groups of the spread placement (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
@@ -214,7 +215,8 @@ def main() -> int:
     grad_sets = int(max(1, min(total_steps, (0.45 * free - base_need) // per_set + 1)))
     t_setup = time.perf_counter()
     dw = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk" if args.bulk_init else True,
-                                placement=args.placement, grad_sets=grad_sets)
+                                placement=args.placement, grad_sets=grad_sets,
+                                spread_gap=(args.spread_gap_gib << 30) or None)
     fill = dw.fill_gradients_bulk if args.bulk_grad else dw.fill_gradients
     for g in range(grad_sets):
         fill(g + 1, g)                            # step k reads set (k - 1) mod grad_sets

@@ -53,7 +53,8 @@ class DeviceWorkload:
 
     def __init__(self, wl: Workload, device: str = "cuda:0", base_seed: int = workloads.BASE_SEED,
                  init=True, layout: Optional[dict] = None, skew_bytes: Optional[dict] = None,
-                 single_allocation=False, placement: str = "auto", grad_sets: int = 1):
+                 single_allocation=False, placement: str = "auto", grad_sets: int = 1,
+                 spread_gap: Optional[int] = None):
         """`layout`: hyper-parameter overrides that are fixed for the life of the plan (opt, mode, ...).
         In the master-weight mode the fp32 initial weights are kept as the master copy; in the
         exact-injection mode the aux buffer starts as e_0 = theta_0 - q(theta_0) (Appendix A).
@@ -80,7 +81,7 @@ class DeviceWorkload:
             ngaps = 3 if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER) else 2
             torch.cuda.empty_cache()
             free = torch.cuda.mem_get_info(dev)[0]
-            gap = min(self.SPREAD_GAP, max(0, int(0.7 * free) - need) // ngaps) >> 21 << 21
+            gap = min(spread_gap or self.SPREAD_GAP, max(0, int(0.7 * free) - need) // ngaps) >> 21 << 21
             if gap >= (24 << 30) and (placement == "spread" or need >= self.SPREAD_MIN_BYTES):
                 skew = {"m": gap, "v": gap}
                 if ngaps == 3:
