@@ -158,7 +158,8 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan);
  * 512-element tiles of block-scaled tensors, one over their ragged tails if any, one per workgroup size for wide
  * groups, and four for tensors with a single scale (abs-max pass into the plan's scratch, its reduction, apply
  * pass, scale write).  Steps of one plan that use that scratch must not overlap each other on different streams.
- * hp->block_size, state_dtype, scale_dtype, opt and mode must equal the plan's.
+ * hp->block_size, state_dtype, scale_dtype, opt and mode must equal the plan's, and the device that was current at
+ * eco_plan_create must be current (ECO_EINVAL otherwise).
  */
 eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream);
 

@@ -152,6 +152,7 @@ struct eco_plan {
   uint32_t block_size = 0;
   int32_t state_dtype = 0, scale_dtype = 0, opt = 0, mode = 0;
   int cus = 256;
+  int device = 0;    // the device that was current when the plan was created (its tables live there)
   Group groups[4];   // indexed by eco_format_t
 };
 
@@ -293,6 +294,10 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   }
   if (st != ECO_OK) { delete plan; return st; }
 
+  {
+    const hipError_t e = hipGetDevice(&plan->device);
+    if (e != hipSuccess) { delete plan; return fail_hip(e, "hipGetDevice"); }
+  }
   plan->cus = num_compute_units();
   for (Group &g : plan->groups) {
     if (g.descs.empty()) continue;
@@ -339,6 +344,9 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
   if (hp->block_size != plan->block_size || hp->state_dtype != plan->state_dtype || hp->scale_dtype != plan->scale_dtype ||
       hp->opt != plan->opt || hp->mode != plan->mode)
     return fail(ECO_EINVAL, "step: block_size, state_dtype, scale_dtype, opt and mode must equal the plan's");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->device)
+    return fail(ECO_EINVAL, "step: the plan was created on device %d, which is not the current device (%d)", plan->device, dev);
 
   eco_constants_t c;
   derive_constants(hp, &c);
@@ -403,6 +411,7 @@ static eco_status_t check_flat(const void *weights, const void *scales, uint64_t
   if (fmt != ECO_FMT_FP8_E4M3 && fmt != ECO_FMT_INT4) return fail(ECO_EINVAL, "format %d is not a quantized format", fmt);
   if (!is_dtype(scale_dtype)) return fail(ECO_EINVAL, "unknown scale dtype");
   if (numel == 0) return fail(ECO_EINVAL, "numel == 0");
+  if (numel > (1ull << 40)) return fail(ECO_EUNSUPPORTED, "more than 2^40 elements in one call");
   if (group_size == 0) return fail(ECO_EINVAL, "group_size must be positive");
   if (!weights || !scales) return fail(ECO_EINVAL, "null weights or scales");
   if (!aligned16(weights) || !aligned16(scales)) return fail(ECO_EALIGN, "weights and scales must be 16-byte aligned");
