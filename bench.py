@@ -74,6 +74,24 @@ def profiled_traffic(wl_name: str):
     return None
 
 
+def static_bytes_per_param(wl, variant: str) -> float:
+    """Bytes of weights + optimizer state resident per parameter (the paper's memory accounting, Sec. 4.2
+    "Memory and Runtime": 12 B with fp32 master weights, m and v; 9 B with FP8 weights, m and v)."""
+    st = 2 if wl.state_bf16 else 4
+    sc = 2 if wl.scale_bf16 else 4
+    total = 0.0
+    for t in wl.tensors:
+        if t.fmt in ("fp8", "int4"):
+            b = (1.0 if t.fmt == "fp8" else 0.5) + sc / t.group_size(wl.block_size)
+        else:
+            b = 2.0
+        b += st * (2 if variant.startswith("adam") else 1)
+        if "master" in variant or "exact" in variant:
+            b += 4.0
+        total += b * t.numel
+    return total / wl.numel
+
+
 def cpu_baseline(wl, target_seconds: float = 10.0) -> dict:
     """The CPU oracle, as it stands, timed on a bounded sample of the same workload (host cores of this machine)."""
     import numpy as np
@@ -262,6 +280,7 @@ def main() -> int:
                               if args.config != 5 else "int4 codes, %s bf16 scales, bf16 gradients, bf16 m and v")
                    % {"block": "block-128", "row": "row-wise", "tensor": "tensor-wise"}[args.granularity],
                    "optimizer": args.variant,
+                   "static_bytes_per_param": round(static_bytes_per_param(wl, args.variant), 4),
                    "launches_per_step": {"block": 1 if args.config != 2 else 2, "row": "one per row length",
                                          "tensor": "two passes, a reduction and a scale kernel"}[args.granularity]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
