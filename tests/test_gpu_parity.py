@@ -337,6 +337,26 @@ def test_results_do_not_depend_on_launch_geometry_or_plan_order(harness, eco):
     assert _equal(results[0], results[1]) and _equal(results[0], results[2])
 
 
+def test_results_do_not_depend_on_where_the_arenas_lie(harness, eco):
+    """The spread placement (one allocation, arena groups tens of GiB apart) and resident gradient sets (one plan
+    per set over the same weights and state) are layout only: same bytes as separate allocations and one set."""
+    wl = small_mixed_workload("fp8")
+    a = harness.DeviceWorkload(wl, DEV, placement="packed")
+    b = harness.DeviceWorkload(wl, DEV, placement="spread", grad_sets=3)
+    assert a.placement == "packed" and "GiB apart" in b.placement
+    assert b.m.data_ptr() - b.grad.data_ptr() > (20 << 30) and b.v.data_ptr() - b.m.data_ptr() > (20 << 30)
+    for k in (1, 2, 3):
+        b.fill_gradients(k, k - 1)
+    for k in (1, 2, 3):
+        a.fill_gradients(k)
+        a.step(k)
+        b.step(k, k - 1)
+    torch.cuda.synchronize()
+    assert _equal(_snapshot(a), _snapshot(b))
+    a.close()
+    b.close()
+
+
 def test_plan_less_entry_point_and_resume(harness, eco):
     """eco_step_tensors gives the same bytes as a plan; and because the state is only (codes, scales,
     m, v) plus (seed, step), stopping after 2 steps and continuing equals 4 steps in a row."""
