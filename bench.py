@@ -165,6 +165,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="workload number (1-5) of the baseline's configs")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning: workgroups per compute unit (0 = default)")
     ap.add_argument("--lds-bytes", type=int, default=-1, help="launch tuning: dynamic LDS per workgroup (-1 = default)")
+    ap.add_argument("--lds-bytes-wave", type=int, default=-1,
+                    help="launch tuning: dynamic LDS per wave of the wide-group and tensor-wise kernels (-1 = default)")
     ap.add_argument("--variant", default="adam-sr",
                     choices=["adam-sr", "adam-rtn", "sgdm-sr", "sgdm-rtn", "adam-naive-sr", "adam-master-sr",
                              "adam-master-rtn", "sgdm-master-sr", "sgdm-exact-sr"],
@@ -209,6 +211,8 @@ def main() -> int:
         eco.eco_set_option(0, args.wgs_per_cu)
     if args.lds_bytes >= 0:
         eco.eco_set_option(1, args.lds_bytes)
+    if args.lds_bytes_wave >= 0:
+        eco.eco_set_option(2, args.lds_bytes_wave)
 
     wl = workloads.CONFIGS[args.config]()
     if args.granularity != "block":

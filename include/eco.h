@@ -202,7 +202,8 @@ eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out);
  *   option 0: cap on the step kernel's grid, in workgroups per compute unit; the kernel then loops over
  *             tiles (0 = library default: one workgroup per 512-element tile, no cap)
  *   option 1: bytes of dynamic LDS requested per workgroup of the step kernel (-1 = library default).
- *             The kernel never touches it; the request only caps resident workgroups per compute unit. */
+ *             The kernel never touches it; the request only caps resident workgroups per compute unit.
+ *   option 2: the same per wave of the wide-group and tensor-wise kernels (-1 = library default) */
 eco_status_t eco_set_option(int32_t option, int64_t value);
 
 const char *eco_status_string(eco_status_t status);

@@ -18,6 +18,7 @@ namespace {
 thread_local std::string g_last_error;
 int64_t g_wgs_per_cu = 0;   // 0 = default
 int64_t g_lds_bytes = -1;    // -1 = default; dynamic LDS per workgroup of the step kernel (occupancy limiter)
+int64_t g_lds_bytes_wave = -1;   // -1 = default; the same per wave of the wide-group and tensor-wise kernels
 
 eco_status_t fail(eco_status_t st, const char *fmt, ...) {
   char buf[512];
@@ -115,21 +116,24 @@ int num_compute_units() {
   return cus;
 }
 
-// Resident waves per compute unit at which the step kernel measured fastest on MI355X, by bytes moved per
-// 512-element tile (fp32 state: the kernel is bound by HBM, which delivers most with roughly 100-120 KB of
-// tile traffic in flight per compute unit; bf16 state: bound by instruction issue, no cap), expressed as
-// the dynamic-LDS request that produces the cap (160 KB of LDS per compute unit).
-uint32_t default_lds_bytes(const eco::KernelVariant &kv) {
+// Resident waves per compute unit at which the full-tile step kernel measured fastest on MI355X, by bytes
+// moved per 512-element tile (fp32 state: the kernel is bound by HBM, which delivers most with roughly
+// 100-120 KB of tile traffic in flight per compute unit; bf16 state: bound by instruction issue, no cap: 0).
+int default_waves(const eco::KernelVariant &kv) {
   if (kv.state_bf16 || kv.fmt == eco::FMT_BF16_PLAIN || kv.fmt == eco::FMT_FP32_ID) return 0;
-  int waves;
   switch (kv.algo) {
-    case eco::ALGO_ADAM: waves = 11; break;          // 20.1 B/parameter
-    case eco::ALGO_ADAM_MASTER: waves = 8; break;    // 27.0
-    case eco::ALGO_SGDM: waves = 14; break;          // 12.1
-    case eco::ALGO_SGDM_MASTER: waves = 10; break;   // 19.0
-    default: waves = 11; break;                      // SGDM with a stored error: 20.1
+    case eco::ALGO_ADAM: return 11;          // 20.1 B/parameter
+    case eco::ALGO_ADAM_MASTER: return 8;    // 27.0
+    case eco::ALGO_SGDM: return 14;          // 12.1
+    case eco::ALGO_SGDM_MASTER: return 10;   // 19.0
+    default: return 11;                      // SGDM with a stored error: 20.1
   }
-  return static_cast<uint32_t>(163840 / waves / 512 * 512);
+}
+
+// The cap is expressed as a dynamic-LDS request the kernels never touch (160 KB of LDS per compute unit).
+// For Adam the wide-group kernel measured best at the same cap, the two tensor-wise passes with three waves more.
+uint32_t lds_for_waves(int waves, int granule) {
+  return waves > 0 ? static_cast<uint32_t>(163840 / waves / granule * granule) : 0u;
 }
 
 // Default: one workgroup per tile.  The hardware dispatcher then hands out tiles in address order,
@@ -183,6 +187,11 @@ eco_status_t eco_set_option(int32_t option, int64_t value) {
   if (option == 1) {
     if (value < -1 || value > 65536) return fail(ECO_EINVAL, "LDS bytes per workgroup must lie in [-1, 65536]");
     g_lds_bytes = value;
+    return ECO_OK;
+  }
+  if (option == 2) {
+    if (value < -1 || value > 32768) return fail(ECO_EINVAL, "LDS bytes per wave must lie in [-1, 32768]");
+    g_lds_bytes_wave = value;
     return ECO_OK;
   }
   return fail(ECO_EINVAL, "unknown option %d", option);
@@ -385,7 +394,12 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     else if (hp->mode == ECO_MODE_EXACT) kv.algo = eco::ALGO_SGDM_EXACT;
     else kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM : eco::ALGO_SGDM;
     kv.round = hp->round;
-    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes) : default_lds_bytes(kv);
+    const int waves = default_waves(kv);
+    const int waves_wide = kv.algo == eco::ALGO_ADAM ? waves : 0;     // measured for Adam only; SGDM ran best uncapped
+    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes) : lds_for_waves(waves, 512);
+    a.lds_bytes_wave = g_lds_bytes_wave >= 0 ? static_cast<uint32_t>(g_lds_bytes_wave) : lds_for_waves(waves_wide, 256);
+    a.lds_bytes_tw = g_lds_bytes_wave >= 0 ? static_cast<uint32_t>(g_lds_bytes_wave)
+                                           : lds_for_waves(waves_wide ? waves_wide + 3 : 0, 256);
     const hipError_t e = eco::launch_step(kv, a, grid_for(a.num_tiles, plan->cus), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "step kernel launch");
   }

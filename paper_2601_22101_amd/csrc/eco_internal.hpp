@@ -64,6 +64,8 @@ struct StepArgs {            // by-value kernel argument: everything wave-unifor
   uint32_t seed_lo, seed_hi, step_lo;
   // host side only
   uint32_t lds_bytes;              // dynamic LDS per workgroup of the full-tile kernel (occupancy cap)
+  uint32_t lds_bytes_wave;         // the same per wave of the wide-group kernel
+  uint32_t lds_bytes_tw;           // the same per (one-wave) workgroup of the two tensor-wise passes
   const uint32_t *wide_base;       // wide-group lists, one per workgroup size, back to back
   uint32_t wide_offset[MAX_WIDE_WAVES + 1];
   uint32_t num_wide[MAX_WIDE_WAVES + 1];

@@ -484,6 +484,8 @@ __global__ __launch_bounds__(WG_THREADS) void eco_tensorwise_scale_kernel(const 
   else static_cast<float *>(td.s)[0] = s_new;
 }
 
+inline unsigned lds_cap(unsigned bytes) { return bytes < 65536u ? bytes : 65536u; }   // per-workgroup request limit
+
 template <int FMT, bool STATE_BF16, bool SC, int RD>
 void launch_step_algos(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
 #define ECO_LAUNCH(AL)                                                                                            \
@@ -499,15 +501,15 @@ void launch_step_algos(const KernelVariant &kv, const StepArgs &args, unsigned g
       StepArgs wa = args;                                                                                         \
       wa.wide_tensor = args.wide_base + args.wide_offset[nw];                                                     \
       hipLaunchKernelGGL((eco_step_wide_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_wide[nw]),            \
-                         dim3(64 * nw), 0, stream, wa);                                                           \
+                         dim3(64 * nw), lds_cap(args.lds_bytes_wave * nw), stream, wa);                           \
     }                                                                                                             \
     if (args.num_tw_tiles) {                                                                                      \
       hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_TILE>),                     \
-                         dim3(args.num_tw_tiles), dim3(WG_THREADS), 0, stream, args);                             \
+                         dim3(args.num_tw_tiles), dim3(WG_THREADS), args.lds_bytes_tw, stream, args);             \
       hipLaunchKernelGGL((eco_tensorwise_reduce_kernel<FMT>), dim3(args.num_tw_tensors), dim3(TW_REDUCE_THREADS), \
                          0, stream, args);                                                                        \
       hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_SLOT>),                     \
-                         dim3(args.num_tw_tiles), dim3(WG_THREADS), 0, stream, args);                             \
+                         dim3(args.num_tw_tiles), dim3(WG_THREADS), args.lds_bytes_tw, stream, args);             \
       hipLaunchKernelGGL((eco_tensorwise_scale_kernel<FMT, SC>),                                                  \
                          dim3((args.num_tw_tensors + WG_THREADS - 1) / WG_THREADS), dim3(WG_THREADS), 0, stream,  \
                          args);                                                                                   \
