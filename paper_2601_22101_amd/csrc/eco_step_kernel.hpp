@@ -299,9 +299,15 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
     if (WRITE) store_state8<STATE_BF16, ACC>(td.v, e0, nvalid, v);   // v is final (Alg. 3 returns it unchanged)
     sqrt_plus_eps8(x, a.eps, d);
   }
+  if (a.wd != 0.0f) {
+    // decoupled decay; off in most runs, so it is kept a (wave-uniform) branch: the empty asm statement
+    // stops the compiler from turning the block into eight multiply-subtract-select triples
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[j] = w[j] - a.wd * w[j];
+  }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    float wj = w[j];
     float u;
     if (ADAM) {
       u = (a.c1 * m[j]) / d[j];
@@ -310,8 +316,7 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
       d[j] = 0.0f;
       u = a.lr * m[j];
     }
-    if (a.wd != 0.0f) wj = wj - a.wd * wj;
-    th[j] = wj - u;
+    th[j] = w[j] - u;
     if (ACC != ACC_FULL && j >= nvalid) th[j] = 0.0f;
   }
 
