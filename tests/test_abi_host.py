@@ -163,3 +163,37 @@ def test_product_package_never_reaches_the_oracle():
                 text = open(os.path.join(dirpath, fn)).read()
                 assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), fn
                 assert "eco_oracle" not in text and "liboracle" not in text, fn
+
+
+def test_harness_arena_layout_is_aligned_and_fits_its_pool(eco):
+    """Host logic of the harness: every tensor's slice of every arena starts 256-byte aligned, slices do not
+    overlap, and one allocation of pool_bytes holds all arenas (with any number of gradient sets)."""
+    import workloads
+    from paper_2601_22101_amd.harness import DeviceWorkload as D
+    for wl in (workloads.config2(), workloads.config4(), workloads.config5(),
+               workloads.with_granularity(workloads.config4(), "row"),
+               workloads.with_granularity(workloads.config5(), "tensor")):
+        offs, soffs, coffs, woffs, off, soff, code_bytes, woff = D._layout(wl)
+        st = 2 if wl.state_bf16 else 4
+        sc = 2 if wl.scale_bf16 else 4
+        prev_end = {"e": 0, "s": 0, "c": 0, "w": 0}
+        for t, o, so, co, wo in zip(wl.tensors, offs, soffs, coffs, woffs):
+            assert o % 512 == 0 and o >= prev_end["e"]
+            prev_end["e"] = o + t.numel
+            if t.fmt in ("fp8", "int4"):
+                gs = t.group_size(wl.block_size)
+                assert (so * sc) % 256 == 0 and so >= prev_end["s"]
+                prev_end["s"] = so + (t.numel + gs - 1) // gs
+                assert co % 256 == 0 and co >= prev_end["c"]
+                prev_end["c"] = co + (t.numel if t.fmt == "fp8" else (t.numel + 1) // 2)
+            else:
+                assert wo % 512 == 0 and wo >= prev_end["w"]
+                prev_end["w"] = wo + t.numel
+        assert prev_end["e"] <= off and prev_end["s"] <= max(soff, 1) and prev_end["c"] <= max(code_bytes, 1)
+        for mode, sets in ((eco.ECO_MODE_ECO, 1), (eco.ECO_MODE_MASTER, 1), (eco.ECO_MODE_ECO, 8)):
+            arenas = [max(code_bytes, 1), max(soff, 1) * sc, max(woff, 1) * 2, st * off, st * off] + [2 * off] * sets
+            if mode == eco.ECO_MODE_MASTER:
+                arenas.append(4 * off)
+            # each arena starts on a 2 MiB boundary inside the pool
+            need = sum(-(-a // (1 << 21)) * (1 << 21) for a in arenas) + (1 << 21)
+            assert D.pool_bytes(wl, mode, sets) >= need
