@@ -119,12 +119,17 @@ def test_flat_helpers_validate(eco):
     assert q(bs=100) == eco.ECO_EUNSUPPORTED
     assert q(bs=0) == eco.ECO_EINVAL
     assert q(src=0x1004) == eco.ECO_EALIGN
+    assert q(n=(1 << 40) + 1) == eco.ECO_EUNSUPPORTED          # size guard, before any launch
+    assert q(bs=8200, n=1 << 20) == eco.ECO_EUNSUPPORTED       # wide groups end at 8192 elements ...
+    assert q(bs=20, n=1 << 20) == eco.ECO_EUNSUPPORTED         # ... and are multiples of 8
     assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 1024, 0, 128, 0, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 0, 0x1000, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 16, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_set_option, 5, 1) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_set_option, 0, 100000) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_set_option, 2, 40000) == eco.ECO_EINVAL
     eco.eco_set_option(0, 0)
+    eco.eco_set_option(2, -1)
 
 
 def test_step_constants_follow_the_paper(eco):
