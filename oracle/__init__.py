@@ -20,7 +20,10 @@ from dataclasses import dataclass, field
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "eco_oracle.c")
+# ECO_ORACLE_SOURCE: another C file to build and load instead (the mutation test of the pins plants
+# mistakes in copies of the oracle and checks that the pins notice); its libraries go next to it.
+_SRC = os.environ.get("ECO_ORACLE_SOURCE") or os.path.join(_HERE, "eco_oracle.c")
+_OUT_DIR = os.path.dirname(os.path.abspath(_SRC))
 
 FMT_E4M3, FMT_INT4, FMT_IDENTITY, FMT_ADDNOISE, FMT_BF16_PLAIN = range(5)
 OPT_ADAM, OPT_SGDM = 0, 1
@@ -29,7 +32,7 @@ MODE_NAIVE, MODE_ECO, MODE_EXACT, MODE_MASTER = 0, 1, 2, 3
 
 
 def lib_path(real: str) -> str:
-    return os.path.join(_HERE, f"liboracle_{real}.so")
+    return os.path.join(_OUT_DIR, f"liboracle_{real}.so")
 
 
 def build(force: bool = False) -> None:

@@ -101,14 +101,17 @@ def _neighbours(grid, ay):
 @pytest.mark.parametrize("fmt", [FMT_E4M3, FMT_INT4])
 def test_sr_exhaustive_over_random_field(o32, fmt):
     """For fixed y, sweep all 2^16 values of the element's random field: only the two neighbours
-    occur, and the number of 'up' outcomes is f * 2^16 to within one count (Sec. 3.1)."""
+    occur, and the number of 'up' outcomes is exactly floor(F / 16), F = f * 2^20 rounded to nearest even:
+    the probability of rounding up is proportional to the distance from the lower neighbour (Sec. 3.1) to
+    within 2^-16, and values whose F is a multiple of 16 (f = 1/2, 1/4, 1/16 below) hit it exactly."""
     table = o32.decode_table(fmt)
     grid = sorted(Fraction(float(v)) for v in (table[:127] if fmt == FMT_E4M3 else table[:8]))
     rho = grid[-1]
     rng = np.random.default_rng(7)
     ys = list(rng.uniform(0, float(rho), 12).astype(np.float32))
     ys += [np.float32(2.0 ** -12), np.float32(0.0123), np.float32(float(rho) - 1e-3), np.float32(1.0),
-           np.float32(3.0 + 2.0 ** -20), np.float32(1.5 - 2.0 ** -20)]
+           np.float32(3.0 + 2.0 ** -20), np.float32(1.5 - 2.0 ** -20),
+           np.float32(1.0625), np.float32(2.5), np.float32(3.25), np.float32(5.0625), np.float32(6.5)]
     r = np.arange(65536, dtype=np.uint16)
     for y in ys:
         for sign in (1, -1):
@@ -118,7 +121,8 @@ def test_sr_exhaustive_over_random_field(o32, fmt):
             assert set(np.unique(vals)) <= {float(lo), float(hi)}
             f = (Fraction(float(y)) - lo) / (hi - lo)
             ups = int((vals == float(hi)).sum()) if hi != lo else 0
-            assert abs(ups - f * 65536) <= 1, (float(y), ups, float(f * 65536))
+            assert ups == round(f * 2 ** 20) // 16, (float(y), ups, float(f * 65536))
+            assert abs(ups - f * 65536) <= 1
             if f == 0:
                 assert ups == 0
             # sign symmetry: the magnitude decision does not depend on the sign

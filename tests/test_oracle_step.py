@@ -369,3 +369,39 @@ def test_invalid_arguments_are_rejected(o32):
         assert o32.eco_step(cfg, n, m, v, codes=codes, scales=scales, grad_bf16=g) != 0, bad
     assert o32.eco_step(ok, n, m, None, codes=codes, scales=scales, grad_bf16=g) != 0
     assert o32.eco_step(ok, n, m, v, codes=None, scales=scales, grad_bf16=g) != 0
+
+
+@pytest.mark.parametrize("fmt,rho", [(FMT_E4M3, 448.0), (FMT_INT4, 7.0)])
+def test_step_gives_every_element_its_documented_random_field(o32, fmt, rho):
+    """Inside the step, element i of the tensor (span offset included) rounds with the 16-bit field i & 7 of
+    Philox call q = i >> 3, counter (q, step, tensor_id), key = seed: the new codes are recomputed here from
+    theta~ with an independent big-integer Philox and the separately pinned encoder."""
+    from test_oracle_random import philox_bigint
+    rng = np.random.default_rng(11)
+    n, bs, off = 96, 32, 64
+    seed, step, tid = 0xFEDCBA9876543210, 5, 9
+    w0 = (rng.standard_normal(n) * 0.05).astype(np.float32)
+    codes, scales = o32.quantize_rtn(fmt, w0, block_size=bs)
+    g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    m = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    v = (rng.random(n) * 1e-4).astype(np.float32)
+    theta = np.zeros(n, np.float32)
+    cfg = StepConfig(fmt=fmt, opt=OPT_ADAM, round=ROUND_SR, block_size=bs, lr=1e-2, step=step, seed=seed,
+                     tensor_id=tid, elem_offset=off)
+    assert o32.eco_step(cfg, n, m, v, codes=codes, scales=scales, grad_real=g, dbg_theta=theta) == 0
+    r16 = np.zeros(n, np.uint16)
+    for i in range(n):
+        gi = off + i
+        words = philox_bigint([gi >> 3, 0, step, tid], [seed & 0xFFFFFFFF, seed >> 32])
+        word = words[(gi & 7) >> 1]
+        r16[i] = (word >> 16) if gi & 1 else (word & 0xFFFF)
+    expect = np.zeros(n, np.uint8)
+    for b in range(n // bs):
+        th = theta[b * bs:(b + 1) * bs]
+        inv = np.float32(rho) / np.abs(th).max()
+        expect[b * bs:(b + 1) * bs] = o32.encode(fmt, ROUND_SR, (th * inv).astype(np.float32), r16[b * bs:(b + 1) * bs])
+    got = codes if fmt == FMT_E4M3 else np.stack([codes & 15, codes >> 4], axis=1).reshape(-1)[:n]
+    assert np.array_equal(got, expect)
+    # the decision really depends on the field: other random bits give other codes somewhere
+    assert not np.array_equal(o32.encode(fmt, ROUND_SR, (theta * (np.float32(rho) / np.abs(theta[:bs]).max())).astype(np.float32)[:bs],
+                                         np.roll(r16[:bs], 1)), expect[:bs])
