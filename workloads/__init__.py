@@ -67,9 +67,11 @@ class Workload:
         return sum(t.numel for t in self.tensors)
 
     def lr_at(self, k: int) -> float:
+        """Learning rate of step k (1-based); a cosine schedule runs over the workload's `steps` steps and
+        starts again after them, so that runs longer than the configuration keep a positive rate."""
         if not self.cosine_lr:
             return self.lr
-        return self.lr * 0.5 * (1.0 + math.cos(math.pi * (k - 1) / self.steps))
+        return self.lr * 0.5 * (1.0 + math.cos(math.pi * ((k - 1) % self.steps) / self.steps))
 
 
 def config1() -> Workload:
