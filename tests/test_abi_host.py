@@ -202,3 +202,29 @@ def test_harness_arena_layout_is_aligned_and_fits_its_pool(eco):
             # each arena starts on a 2 MiB boundary inside the pool
             need = sum(-(-a // (1 << 21)) * (1 << 21) for a in arenas) + (1 << 21)
             assert D.pool_bytes(wl, mode, sets) >= need
+
+
+def test_a_plain_c_client_compiles_links_and_runs(eco, tmp_path):
+    """include/eco.h is valid C99 (-Wall -Wextra -pedantic -Werror), libeco.so links by its C names, and the
+    host-only entry points give a C caller what they give the Python binding."""
+    import subprocess
+    lib_dir = os.path.join(ROOT, "paper_2601_22101_amd")
+    exe = str(tmp_path / "abi_host")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "native", "abi_host.c"), "-o", exe, "-L", lib_dir, "-l:libeco.so",
+           f"-Wl,-rpath,{lib_dir}"]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout
+    out = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert out.returncode == 0, out.stdout
+    lines = dict(l.split(" ", 1) for l in out.stdout.strip().splitlines())
+    assert lines["version"] == str(eco.eco_version())
+    assert lines["sizes"] == "72 80 52"
+    vals = lines["constants"].split()
+    assert vals[0] == "0"
+    hp = eco.make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=3, seed=7, block_size=128)
+    c = eco.eco_step_constants(hp)
+    ref = [c.b1, c.omb1, c.b2, c.omb2, c.rbc2, c.c1, c.eps, c.kappa]
+    assert [np.float32(float(x)) for x in vals[1:]] == [np.float32(x) for x in ref]
+    assert lines["step0"].startswith(f"{eco.ECO_EINVAL} invalid argument |") and "1-based" in lines["step0"]
+    assert lines["nullplan"] == str(eco.ECO_EINVAL) and lines["destroynull"] == "0"
