@@ -211,13 +211,18 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan) {
   for (Group &g : plan->groups) any = any || g.d_descs || g.d_tables;
   eco_status_t st = ECO_OK;
   if (any) {
+    // steps may still be running on the plan's device: wait for that device, whichever is current
+    int cur = -1;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    if (have_cur && cur != plan->device) (void)hipSetDevice(plan->device);
     const hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) st = fail_hip(e, "hipDeviceSynchronize");
-  }
-  for (Group &g : plan->groups) {
-    if (g.d_descs) (void)hipFree(g.d_descs);
-    if (g.d_tables) (void)hipFree(g.d_tables);
-    if (g.d_tile_max) (void)hipFree(g.d_tile_max);
+    for (Group &g : plan->groups) {
+      if (g.d_descs) (void)hipFree(g.d_descs);
+      if (g.d_tables) (void)hipFree(g.d_tables);
+      if (g.d_tile_max) (void)hipFree(g.d_tile_max);
+    }
+    if (have_cur && cur != plan->device) (void)hipSetDevice(cur);
   }
   delete plan;
   return st;
