@@ -122,7 +122,7 @@ int num_compute_units() {
 int default_waves(const eco::KernelVariant &kv) {
   if (kv.state_bf16 || kv.fmt == eco::FMT_BF16_PLAIN || kv.fmt == eco::FMT_FP32_ID) return 0;
   switch (kv.algo) {
-    case eco::ALGO_ADAM: return 11;          // 20.1 B/parameter
+    case eco::ALGO_ADAM: return 12;          // 20.1 B/parameter
     case eco::ALGO_ADAM_MASTER: return 8;    // 27.0
     case eco::ALGO_SGDM: return 14;          // 12.1
     case eco::ALGO_SGDM_MASTER: return 10;   // 19.0

@@ -286,6 +286,8 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
     w[6] = decode_elem<FMT, 6>(c) * s_old; w[7] = decode_elem<FMT, 7>(c) * s_old;
   }
 
+  __builtin_amdgcn_s_setprio(0);      // loads issued: back to the default priority (see eco_step_kernel)
+
   // OPTIM_STEP on the de-quantized (or master) weights
   float th[8], d[8];
   if (ADAM) {
@@ -402,6 +404,11 @@ __device__ __forceinline__ TensorDesc load_tensor_desc(const StepArgs &a, uint32
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(WG_THREADS, 8) void eco_step_kernel(const StepArgs a) {
   for (uint32_t tile = blockIdx.x; tile < a.num_tiles; tile += gridDim.x) {
+    // A wave that has not issued its loads yet goes first: its address arithmetic and load instructions
+    // are not queued behind the arithmetic of the waves that already have their data (the priority is
+    // dropped again in step_lane, once the loads are issued).  Measured: +0.3 % and a flatter optimum
+    // over the occupancy cap.
+    __builtin_amdgcn_s_setprio(3);
     const TensorDesc td = load_tensor_desc(a, load_table(a.tile_tensor, tile));
     const uint64_t e0 = (uint64_t)(tile - td.first_unit) * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
     const bool writer = (threadIdx.x & ((1u << (td.bs_shift - 3)) - 1u)) == 0;
