@@ -437,6 +437,7 @@ __global__ __launch_bounds__(WG_THREADS) void eco_step_ragged_kernel(const StepA
 // ceil(group/512) waves per group, abs-max by wave all-reduce plus an LDS combine across the waves.
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
+  __builtin_amdgcn_s_setprio(3);      // as in eco_step_kernel: loading waves first
   const TensorDesc td = load_tensor_desc(a, load_table(a.wide_tensor, blockIdx.x));
   const uint64_t grp = blockIdx.x - td.first_unit;
   const uint64_t start = grp * td.group_size;
@@ -457,6 +458,7 @@ __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
 // kernel writes the new scales.
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, int RED>
 __global__ __launch_bounds__(WG_THREADS) void eco_step_tensorwise_kernel(const StepArgs a) {
+  __builtin_amdgcn_s_setprio(3);      // as in eco_step_kernel: loading waves first
   const TensorDesc td = load_tensor_desc(a, load_table(a.tw_tile_tensor, blockIdx.x));
   const uint64_t tile_off = (uint64_t)(blockIdx.x - td.first_unit) * TILE_ELEMS;
   const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
