@@ -357,6 +357,37 @@ def test_results_do_not_depend_on_where_the_arenas_lie(harness, eco):
     b.close()
 
 
+@pytest.mark.parametrize("which", ["blocks", "wide_and_tensorwise"])
+def test_step_can_be_captured_in_a_hip_graph(harness, eco, which):
+    """eco_step allocates nothing, never synchronizes and clears no memory with memset nodes, so a stream
+    capture records it (all its kernels, the tensor-wise scratch passes included).  Each replay is one more
+    step with the captured hyper-parameters; every replay is compared with the same step issued eagerly,
+    with eager work and synchronizations between the replays."""
+    wl = small_mixed_workload("fp8") if which == "blocks" else wide_group_workload("fp8")
+    a = harness.DeviceWorkload(wl, DEV)
+    b = harness.DeviceWorkload(wl, DEV)
+    a.fill_gradients(1)
+    b.fill_gradients(1)
+    b.step(1)                                   # warm-up outside the capture (loads the code objects)
+    a.step(1)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        b.step(1)
+    torch.cuda.synchronize()
+    assert _equal(_snapshot(a), _snapshot(b))   # capturing executed nothing
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for _ in range(3):
+        graph.replay()
+        a.step(1)
+        torch.cuda.synchronize()
+        assert _equal(_snapshot(a), _snapshot(b))
+        scratch.add_(1.0)                       # unrelated eager work between the replays
+        torch.cuda.synchronize()
+    a.close()
+    b.close()
+
+
 def test_plan_less_entry_point_and_resume(harness, eco):
     """eco_step_tensors gives the same bytes as a plan; and because the state is only (codes, scales,
     m, v) plus (seed, step), stopping after 2 steps and continuing equals 4 steps in a row."""
