@@ -180,7 +180,8 @@ eco_status_t eco_step_tensors(const eco_tensor_t *tensors, size_t n, const eco_h
 eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint64_t group_size,
                                int32_t scale_dtype, void *weights, void *scales, void *stream);
 
-/* eco_dequantize — dst[i] = dec(code_i) * scale[i / group_size] as fp32 (Sec. 3.1, x^ = s*y); group_size >= 8.
+/* eco_dequantize — dst[i] = dec(code_i) * scale[i / group_size] as fp32 (Sec. 3.1, x^ = s*y); group_size >= 8,
+ * or one group over the whole tensor.
  * Asynchronous. */
 eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint64_t group_size,
                             int32_t scale_dtype, float *dst, void *stream);

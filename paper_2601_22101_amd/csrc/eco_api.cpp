@@ -458,7 +458,8 @@ eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t nu
   if (st != ECO_OK) return st;
   if (!dst) return fail(ECO_EINVAL, "null destination");
   if (!aligned16(dst)) return fail(ECO_EALIGN, "destination must be 16-byte aligned");
-  if (group_size < 8) return fail(ECO_EUNSUPPORTED, "scale groups of fewer than 8 elements are not supported");
+  if (group_size < 8 && group_size < numel)      // a single group over a tiny tensor is fine
+    return fail(ECO_EUNSUPPORTED, "scale groups of fewer than 8 elements are not supported");
   const hipError_t e = eco::launch_dequantize(weights, scales, numel, fmt, group_size, scale_dtype == ECO_DT_BF16, dst,
                                               static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ECO_OK : fail_hip(e, "dequantize kernel launch");

@@ -337,6 +337,42 @@ def test_results_do_not_depend_on_launch_geometry_or_plan_order(harness, eco):
     assert _equal(results[0], results[1]) and _equal(results[0], results[2])
 
 
+def _random_plan(rng, fmt):
+    """A random tensor list for one plan: awkward and boundary sizes, every class of scale group."""
+    T = workloads.TensorSpec
+    ts = []
+    for i in range(int(rng.integers(1, 7))):
+        kind = rng.choice(["block", "row", "tensor", "plain"], p=[0.4, 0.3, 0.2, 0.1])
+        if kind == "row":
+            cols = int(rng.choice([8, 24, 96, 128, 512, 520, 1000, 1024, 2048, 4096, 4104, 8184, 8192]))
+            shape = (int(rng.integers(1, 9)), cols)
+        else:
+            n = int(rng.choice([1, 7, 8, 127, 128, 511, 512, 513, 4095, 4096, 8191, 8192, 8193, 8200, 20000,
+                                int(rng.integers(1, 60000))]))
+            shape = (n,)
+        if kind == "plain":
+            ts.append(T(f"p{i}", shape, "bf16_plain"))
+        else:
+            ts.append(T(f"{kind}{i}", shape, fmt, grad_std=float(10.0 ** rng.uniform(-4, -2)), granularity=kind))
+    return ts
+
+
+@pytest.mark.parametrize("seed", range(96))
+def test_randomized_plans(harness, eco, o32, seed):
+    """Seeded random plans: random tensor lists (block, row-wise and tensor-wise groups mixed), block size,
+    state and scale types, optimizer, mode, rounding and decay; two steps each, every tensor against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    fmt = "fp8" if rng.random() < 0.5 else "int4"
+    opt = int(rng.integers(0, 2))
+    mode = int(rng.choice([eco.ECO_MODE_NAIVE, eco.ECO_MODE_ECO, eco.ECO_MODE_MASTER] + ([eco.ECO_MODE_EXACT] if opt == 1 else [])))
+    over = dict(opt=opt, mode=mode, round=int(rng.integers(0, 2)), weight_decay=float(rng.choice([0.0, 0.05])),
+                lr=float(rng.choice([1e-3, 3e-2])), beta1=float(rng.choice([0.9, 0.5])), seed=int(rng.integers(0, 2 ** 63)))
+    wl = workloads.Workload(f"rand{seed}", _random_plan(rng, fmt), steps=2, block_size=int(rng.choice([32, 64, 128, 256, 512])),
+                            state_bf16=bool(rng.integers(0, 2)), scale_bf16=bool(rng.integers(0, 2)))
+    worst = _run_with_layout(harness, o32, wl, 2, over)
+    assert worst.get("code_mismatch", 0) == 0 and worst.get("aux_bit_mismatch", 0) == 0, (worst, over, wl)
+
+
 def test_results_do_not_depend_on_where_the_arenas_lie(harness, eco):
     """The spread placement (one allocation, arena groups tens of GiB apart) and resident gradient sets (one plan
     per set over the same weights and state) are layout only: same bytes as separate allocations and one set."""
