@@ -124,8 +124,6 @@ def test_flat_helpers_validate(eco):
     assert q(bs=20, n=1 << 20) == eco.ECO_EUNSUPPORTED         # ... and are multiples of 8
     assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 1024, 0, 128, 0, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 100, 0, 7, 0, 0x3000, 0) == eco.ECO_EUNSUPPORTED
-    # one group over a tiny tensor passes validation (what comes back without a device is the launch error)
-    assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 7, 0, 7, 0, 0x3000, 0) in (eco.ECO_EHIP, eco.ECO_OK)
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 0, 0x1000, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 16, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_set_option, 5, 1) == eco.ECO_EINVAL
