@@ -86,6 +86,41 @@ def test_quantize_init_matches_oracle(eco, o32, fmt, scale_bf16, numel, bs):
     assert np.array_equal(codes.cpu().numpy(), rc)
 
 
+@pytest.mark.parametrize("seed", range(64))
+def test_randomized_quantize_and_dequantize(eco, o32, seed):
+    """Seeded random (length, scale group, source and scale type): the initial quantizer and the dequantizer
+    against the oracle, for every class of group (in-wave block, wide group, whole tensor, ragged ends)."""
+    rng = np.random.default_rng(5000 + seed)
+    fmt = int(rng.integers(0, 2))
+    numel = int(rng.choice([1, 5, 8, 100, 511, 512, 8192, 8193, 12345, int(rng.integers(1, 200000))]))
+    kind = rng.choice(["block", "wide", "tensor"])
+    if kind == "block":
+        gs = int(rng.choice([32, 64, 128, 256, 512]))
+    elif kind == "wide":
+        gs = 8 * int(rng.integers(1, 1025))
+    else:
+        gs = numel + int(rng.integers(0, 3)) * 1000
+    if fmt == 1 and gs % 2 and gs < numel:
+        gs += 1
+    scale_bf16, src_bf16 = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    x = torch.from_numpy((rng.standard_normal(numel) * 10.0 ** rng.uniform(-6, 2)).astype(np.float32))
+    x[rng.integers(0, numel, size=max(1, numel // 50))] = 0.0
+    if src_bf16:
+        x = x.to(torch.bfloat16)
+    ng = (numel + min(gs, numel) - 1) // min(gs, numel)
+    codes = torch.zeros(numel if fmt == 0 else (numel + 1) // 2, dtype=torch.uint8, device=DEV)
+    scales = torch.zeros(ng, dtype=torch.bfloat16 if scale_bf16 else torch.float32, device=DEV)
+    eco.eco_quantize_init(x.to(DEV), int(src_bf16), numel, fmt, gs, int(scale_bf16), codes, scales)
+    rc, rs = o32.quantize_rtn(fmt, x.float().numpy(), block_size=min(gs, numel), scale_bf16=scale_bf16)
+    what = (seed, fmt, numel, gs, scale_bf16, src_bf16)
+    assert np.array_equal(codes.cpu().numpy(), rc), what
+    assert np.array_equal(to_f32(scales).view(np.uint32), rs.view(np.uint32)), what
+    out = torch.zeros(numel, dtype=torch.float32, device=DEV)
+    eco.eco_dequantize(codes, scales, numel, fmt, gs, int(scale_bf16), out)
+    ref = o32.dequantize(fmt, rc, rs, numel, min(gs, numel))
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), what
+
+
 # ---------------------------------------------------------------------------------- whole workloads
 
 def run_workload_parity(harness, o32, wl, steps, base_seed=workloads.BASE_SEED, **over):
