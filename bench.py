@@ -181,6 +181,9 @@ def main() -> int:
                          "with the codes+gradient, m and v arenas tens of GiB apart (spread; auto = spread for workloads "
                          "of 8 GiB and more): arrays streamed in lock-step are faster from different regions of HBM")
     ap.add_argument("--spread-gap-gib", type=int, default=0, help="distance between the arena groups of the spread placement (0 = default)")
+    ap.add_argument("--calibrate-gaps", type=int, default=3,
+                    help="spread placement: time this many candidate distances (the default and smaller ones, 8 GiB apart) "
+                         "in a probe at set-up and keep the fastest (0 or 1 = use the default distance)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
@@ -238,7 +241,7 @@ def main() -> int:
     t_setup = time.perf_counter()
     dw = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk" if args.bulk_init else True,
                                 placement=args.placement, grad_sets=grad_sets,
-                                spread_gap=(args.spread_gap_gib << 30) or None)
+                                spread_gap=(args.spread_gap_gib << 30) or None, calibrate_gaps=args.calibrate_gaps)
     fill = dw.fill_gradients_bulk if args.bulk_grad else dw.fill_gradients
     for g in range(grad_sets):
         fill(g + 1, g)                            # step k reads set (k - 1) mod grad_sets
@@ -280,6 +283,7 @@ def main() -> int:
         "data": "synthetic" if grad_sets >= total_steps else f"synthetic ({grad_sets} gradient sets reused in turn)",
         "config": {"workload": wl.name, "granularity": args.granularity, "tensors": len(wl.tensors), "parameters": wl.numel,
                    "placement": dw.placement,
+                   "placement_probe_gib_ms": dw.calibration,
                    "format": ("fp8_e4m3 codes, %s fp32 scales, bf16 gradients, fp32 m and v"
                               if args.config != 5 else "int4 codes, %s bf16 scales, bf16 gradients, bf16 m and v")
                    % {"block": "block-128", "row": "row-wise", "tensor": "tensor-wise"}[args.granularity],

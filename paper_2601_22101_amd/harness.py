@@ -54,7 +54,7 @@ class DeviceWorkload:
     def __init__(self, wl: Workload, device: str = "cuda:0", base_seed: int = workloads.BASE_SEED,
                  init=True, layout: Optional[dict] = None, skew_bytes: Optional[dict] = None,
                  single_allocation=False, placement: str = "auto", grad_sets: int = 1,
-                 spread_gap: Optional[int] = None):
+                 spread_gap: Optional[int] = None, calibrate_gaps: int = 0):
         """`layout`: hyper-parameter overrides that are fixed for the life of the plan (opt, mode, ...).
         In the master-weight mode the fp32 initial weights are kept as the master copy; in the
         exact-injection mode the aux buffer starts as e_0 = theta_0 - q(theta_0) (Appendix A).
@@ -62,7 +62,11 @@ class DeviceWorkload:
         allocation with the arena groups far apart (see SPREAD_GAP), "auto" = spread for large workloads when
         the device has the memory for it.  `skew_bytes` / `single_allocation` place arenas by hand (probes).
         `grad_sets`: number of gradient arenas (each with a plan of its own over the same weights and state),
-        so that the gradients of several steps can be resident before the steps run back to back."""
+        so that the gradients of several steps can be resident before the steps run back to back.
+        `calibrate_gaps`: with the spread placement, time a few steps (on placeholder data, before the weights
+        are initialised) for this many candidate gaps, the default and smaller ones in steps of 8 GiB, inside
+        the one allocation, and keep the fastest: which distances suit the memory system best differs a little
+        from device to device."""
         self.wl = wl
         self.layout = dict(layout or {})
         self.mode = self.layout.get("mode", eco.ECO_MODE_ECO if self.layout.get("inject", True) else eco.ECO_MODE_NAIVE)
@@ -88,65 +92,100 @@ class DeviceWorkload:
                     skew["aux"] = gap
                 single_allocation = True
                 self.placement = f"one allocation, arena groups {gap >> 30} GiB apart"
-        pool = {"buf": None, "pos": 0}
-        if isinstance(single_allocation, torch.Tensor):      # a caller-owned uint8 pool; skew["pool"] = where to start in it
-            pool["buf"] = single_allocation
-            pool["pos"] = (-pool["buf"].data_ptr()) % (1 << 21) + skew.pop("pool", 0)
+        pool_buf, pool_pos = None, 0
+        external = isinstance(single_allocation, torch.Tensor)
+        if external:                                         # a caller-owned uint8 pool; skew["pool"] = where to start in it
+            pool_buf = single_allocation
+            pool_pos = (-pool_buf.data_ptr()) % (1 << 21) + skew.pop("pool", 0)
         elif single_allocation:
-            pool["buf"] = torch.zeros(self.pool_bytes(wl, self.mode, grad_sets) + sum(skew.values()), dtype=torch.uint8,
-                                      device=dev)
-            pool["pos"] = (-pool["buf"].data_ptr()) % (1 << 21)
+            pool_buf = torch.zeros(self.pool_bytes(wl, self.mode, grad_sets) + sum(skew.values()), dtype=torch.uint8,
+                                   device=dev)
+            pool_pos = (-pool_buf.data_ptr()) % (1 << 21)
+        self._offs = offs
 
-        def arena(kind, n, dtype):
-            """A zeroed arena of n elements.  Separate allocations: its first byte sits skew[kind] bytes (a multiple of
-            256) into its own allocation.  Single allocation: arenas follow each other in one buffer, each starting
-            skew[kind] bytes after a 2 MiB boundary."""
-            k = skew.get(kind, 0)
-            assert k % 256 == 0
-            es = torch.empty(0, dtype=dtype).element_size()
-            if pool["buf"] is not None:
-                start = pool["pos"] + k
-                pool["pos"] = _round_up(start + n * es, 1 << 21)
-                a = pool["buf"][start:start + n * es].view(dtype)
-                if isinstance(single_allocation, torch.Tensor):
-                    a.zero_()
-                return a
-            buf = torch.zeros(n + k // es, dtype=dtype, device=dev)
-            return buf[k // es:]
+        def build_views(skew, zero):
+            """Carve the arenas (separate allocations: the first byte of arena `kind` sits skew[kind] bytes, a
+            multiple of 256, into its own allocation; one allocation: arenas follow each other, each starting
+            skew[kind] bytes after a 2 MiB boundary) and the per-tensor views into them."""
+            pos = [pool_pos]
 
-        self.codes = arena("codes", max(code_bytes, 1), torch.uint8)
-        self.scales = arena("scales", max(soff, 1), self.scale_dtype)
-        self.plain = arena("plain", max(woff, 1), torch.bfloat16)
-        self.grads = [arena("grad", off, torch.bfloat16)]
-        for _ in range(1, grad_sets):
-            self.grads.append(arena("grad_extra", off, torch.bfloat16))
-        self.grad = self.grads[0]
-        self.m = arena("m", off, self.state_dtype)
-        self.v = arena("v", off, self.state_dtype)
-        self.aux = (arena("aux", off, torch.float32)
-                    if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER) else None)
+            def arena(kind, n, dtype):
+                k = skew.get(kind, 0)
+                assert k % 256 == 0
+                es = torch.empty(0, dtype=dtype).element_size()
+                if pool_buf is not None:
+                    start = pos[0] + k
+                    pos[0] = _round_up(start + n * es, 1 << 21)
+                    a = pool_buf[start:start + n * es].view(dtype)
+                    if zero:
+                        a.zero_()
+                    return a
+                buf = torch.zeros(n + k // es, dtype=dtype, device=dev)
+                return buf[k // es:]
 
-        self.tensors: List[TensorViews] = []
-        for i, t in enumerate(wl.tensors):
-            n = t.numel
-            if t.fmt in ("fp8", "int4"):
-                nbytes = n if t.fmt == "fp8" else (n + 1) // 2
-                w = self.codes[coffs[i]:coffs[i] + nbytes]
-                gs = t.group_size(bs)
-                s = self.scales[soffs[i]:soffs[i] + (n + gs - 1) // gs]
-            else:
-                w = self.plain[woffs[i]:woffs[i] + n]
-                s = None
-            o = offs[i]
-            self.tensors.append(TensorViews(t, i, _FMT[t.fmt], w, s, self.grad[o:o + n], self.m[o:o + n],
-                                            self.v[o:o + n], None if self.aux is None else self.aux[o:o + n]))
+            self.codes = arena("codes", max(code_bytes, 1), torch.uint8)
+            self.scales = arena("scales", max(soff, 1), self.scale_dtype)
+            self.plain = arena("plain", max(woff, 1), torch.bfloat16)
+            self.grads = [arena("grad", off, torch.bfloat16)]
+            for _ in range(1, grad_sets):
+                self.grads.append(arena("grad_extra", off, torch.bfloat16))
+            self.grad = self.grads[0]
+            self.m = arena("m", off, self.state_dtype)
+            self.v = arena("v", off, self.state_dtype)
+            self.aux = (arena("aux", off, torch.float32)
+                        if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER) else None)
+            self.tensors = []
+            for i, t in enumerate(wl.tensors):
+                n = t.numel
+                if t.fmt in ("fp8", "int4"):
+                    nbytes = n if t.fmt == "fp8" else (n + 1) // 2
+                    w = self.codes[coffs[i]:coffs[i] + nbytes]
+                    gs = t.group_size(bs)
+                    sc = self.scales[soffs[i]:soffs[i] + (n + gs - 1) // gs]
+                else:
+                    w = self.plain[woffs[i]:woffs[i] + n]
+                    sc = None
+                o = offs[i]
+                self.tensors.append(TensorViews(t, i, _FMT[t.fmt], w, sc, self.grad[o:o + n], self.m[o:o + n],
+                                                self.v[o:o + n], None if self.aux is None else self.aux[o:o + n]))
+
+        self.calibration = None
+        if calibrate_gaps > 1 and pool_buf is not None and not external and "GiB apart" in self.placement:
+            skew = self._calibrate(build_views, pool_buf, skew, calibrate_gaps)
+        build_views(skew, zero=external or self.calibration is not None)
         if init == "bulk":
             self.init_weights_bulk()
         elif init:
             self.init_weights()
-        self._offs = offs
         self.plans = [eco.Plan([self.descriptor(tv, g) for tv in self.tensors], self.hparams(1)) for g in range(grad_sets)]
         self.plan = self.plans[0]
+
+    def _calibrate(self, build_views, pool_buf, skew, n_candidates):
+        """Times the step for the default gap and for smaller ones (steps of 8 GiB, not below 24 GiB) inside
+        the allocation already made, on placeholder contents that are valid for every array kind (the byte
+        0x3C: E4M3 code 1.5, INT4 nibbles 3 and -4, 0.0115 as bf16 and as fp32), and returns the fastest skews.
+        The pool is left dirty: the caller zeroes the arenas it finally carves."""
+        gap = skew["m"]
+        cands = [g for g in (gap - (8 << 30) * k for k in range(n_candidates)) if g >= (24 << 30)]
+        pool_buf.fill_(0x3C)
+        results = []
+        for g in cands:
+            sk = {k: g for k in skew}
+            build_views(sk, zero=False)
+            plan = eco.Plan([self.descriptor(tv) for tv in self.tensors], self.hparams(1))
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            for k in range(1, 5):                       # two warm-up steps, two timed ones
+                plan.step(self.hparams(k))
+                if k >= 2:
+                    ev[k - 2].record()
+            torch.cuda.synchronize(self.device)
+            plan.close()
+            results.append((ev[0].elapsed_time(ev[2]) / 2.0, g))
+        best_ms, best = min(results)
+        self.calibration = [(g >> 30, round(ms, 3)) for ms, g in results]
+        self.placement = (f"one allocation, arena groups {best >> 30} GiB apart (fastest of "
+                          f"{[g >> 30 for g in cands]} GiB in a timing probe at set-up)")
+        return {k: best for k in skew}
 
     @staticmethod
     def _layout(wl: Workload):
