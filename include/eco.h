@@ -40,6 +40,15 @@
  *    of tensors in a plan, or on which tensors share a launch.
  *  - Inputs are assumed finite; behaviour on NaN/Inf is unspecified.
  *  - A plan may be used by one host thread at a time.
+ *
+ * Performance notes for callers (MI355X; none of this changes results)
+ *  - The step is bound by HBM bandwidth.  The arrays of a tensor are streamed in lock-step; on MI355X they
+ *    run several per cent faster when the gradient/code, m and v arrays lie tens of GiB apart in device
+ *    memory (for example in different parts of one large allocation) than when they are packed next to each
+ *    other.
+ *  - One plan over all tensors of a model is one kernel launch per storage format; per-tensor calls pay a
+ *    launch each.
+ *  - Tensor lengths that are multiples of 512 keep every tile on the unguarded fast path.
  */
 #ifndef ECO_H
 #define ECO_H
