@@ -34,12 +34,16 @@
  *  - Weights, scales, m and v are updated in place; gradients are only read.
  *  - Every function returns an eco_status_t; nothing aborts or throws.  After a
  *    failure eco_last_error() (thread-local) describes it, and no kernel of
- *    that call has been launched unless the status is ECO_EHIP.
+ *    that call has been launched unless the status is ECO_EHIP (a launch that
+ *    fails stops the call: kernels enqueued before it still run).  An error
+ *    left pending in the HIP runtime by the caller's earlier work is cleared
+ *    on entry and not reported.
  *  - Results depend only on the inputs, the hyper-parameters, (seed, step,
  *    tensor_id) and the element index: never on launch geometry, on the order
  *    of tensors in a plan, or on which tensors share a launch.
  *  - Inputs are assumed finite; behaviour on NaN/Inf is unspecified.
- *  - A plan may be used by one host thread at a time.
+ *  - A plan may be used by one host thread at a time; eco_set_option may be
+ *    called from any thread.
  *
  * Performance notes for callers (MI355X; none of this changes results)
  *  - The step is bound by HBM bandwidth.  The arrays of a tensor are streamed in lock-step; on MI355X they
@@ -184,7 +188,8 @@ eco_status_t eco_step_tensors(const eco_tensor_t *tensors, size_t n, const eco_h
  *   weights, scales : device outputs, laid out as in eco_tensor_t
  * fmt must be ECO_FMT_FP8_E4M3 or ECO_FMT_INT4; group_size as in eco_tensor_t (not 0).  Asynchronous on `stream`.
  * With one scale for a tensor of more than 8192 elements the abs-max is kept in a library-owned slot between
- * the call's kernels: such calls must not overlap each other on different streams.
+ * the call's kernels; the library hands out 64 such slots in turn and makes a call wait, on its own stream, for
+ * the previous user of its slot, so calls on different streams may overlap.
  */
 eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint64_t group_size,
                                int32_t scale_dtype, void *weights, void *scales, void *stream);
@@ -194,6 +199,17 @@ eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t nume
  * Asynchronous. */
 eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint64_t group_size,
                             int32_t scale_dtype, float *dst, void *stream);
+
+/*
+ * eco_quantize_error — err[i] = src[i] - dec(code_i) * scale[i / group_size] as fp32: the quantization error
+ * e = theta - q(theta) of Sec. 3.1 (notation paragraph) for weights quantized from `src`.  It is the initial
+ * stored error e_0 of the exact-injection mode (Appendix A, Eq. init_im: e_0 = theta_0 - q(theta_0)).
+ *   src : device, numel values of src_dtype; weights, scales: device, as written by eco_quantize_init
+ *   err : device output, numel fp32, 16-byte aligned
+ * group_size >= 8, or one group over the whole tensor.  Asynchronous.
+ */
+eco_status_t eco_quantize_error(const void *src, int32_t src_dtype, const void *weights, const void *scales, uint64_t numel,
+                                int32_t fmt, uint64_t group_size, int32_t scale_dtype, float *err, void *stream);
 
 /*
  * eco_philox_fill — the raw random stream the stochastic rounding of (seed, step, tensor_id) draws from:

@@ -43,8 +43,13 @@
  *     and, on an exact tie, the one with the even code.  Stochastic rounding
  *     forms f = (|y|-lo)/(hi-lo), F = rne(f * 2^20) (f * 2^20 is already an
  *     integer for fp32 y unless |y| lies in the E4M3 subnormal range), and
- *     goes up iff F + 16*r >= 2^20 with r the element's 16 random bits, so
- *     P(up) = floor(F/16) / 2^16, within 2^-16 of f.  |y| >= rho saturates;
+ *     goes up iff F + 16*r + 8 >= 2^20 with r the element's 16 random bits,
+ *     so P(up) = floor((F+8)/16) / 2^16: f rounded to the nearest multiple of
+ *     2^-16 (within 2^-17 of f, and with no preferred direction: Sec. 3.1
+ *     calls stochastic rounding an unbiased estimator and Assumption 3.2 needs
+ *     a zero-mean error; truncating F/16 instead would shrink every weight a
+ *     little at every step).  On-grid values (F = 0) never move.  |y| >= rho
+ *     saturates;
  *   - an all-zero block, or one whose abs-max is so small that rho/max
  *     overflows, is stored as scale 0 / codes 0 and its theta~ goes into e;
  *   - e is measured against the value the next step will reconstruct,
@@ -133,7 +138,7 @@ static int encode_mag(const grid_t *G, double ay, int round, uint32_t r16) {
   if (round == ROUND_SR) {
     f = (ay - G->mag[lo]) / (G->mag[lo + 1] - G->mag[lo]);
     F = nearbyint(f * 1048576.0);
-    up = (F + 16.0 * (double)r16 >= 1048576.0);
+    up = (F + 16.0 * (double)r16 + 8.0 >= 1048576.0);
   } else {
     double below = ay - G->mag[lo], above = G->mag[lo + 1] - ay;   /* exact for fp32 inputs */
     up = (below > above) || (below == above && (lo & 1));

@@ -2,6 +2,7 @@
 // constants, launch plans (device tables mapping tiles to tensors) and kernel dispatch.
 #include <hip/hip_runtime_api.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -16,9 +17,10 @@
 namespace {
 
 thread_local std::string g_last_error;
-int64_t g_wgs_per_cu = 0;   // 0 = default
-int64_t g_lds_bytes = -1;    // -1 = default; dynamic LDS per workgroup of the step kernel (occupancy limiter)
-int64_t g_lds_bytes_wave = -1;   // -1 = default; the same per wave of the wide-group and tensor-wise kernels
+// launch tuning (eco_set_option): read by every eco_step, possibly from other host threads
+std::atomic<int64_t> g_wgs_per_cu{0};        // 0 = default
+std::atomic<int64_t> g_lds_bytes{-1};        // -1 = default; dynamic LDS per workgroup of the step kernel (occupancy limiter)
+std::atomic<int64_t> g_lds_bytes_wave{-1};   // -1 = default; the same per wave of the wide-group and tensor-wise kernels
 
 eco_status_t fail(eco_status_t st, const char *fmt, ...) {
   char buf[512];
@@ -47,6 +49,8 @@ eco_status_t check_block_size(uint32_t bs) {
 
 bool is_dtype(int32_t d) { return d == ECO_DT_FP32 || d == ECO_DT_BF16; }
 
+void derive_constants(const eco_hparams_t *hp, eco_constants_t *c);
+
 // Validation of everything eco_step reads from the hyper-parameters.
 eco_status_t check_hparams(const eco_hparams_t *hp) {
   if (!hp) return fail(ECO_EINVAL, "hyper-parameters: null pointer");
@@ -69,6 +73,13 @@ eco_status_t check_hparams(const eco_hparams_t *hp) {
     if (!(hp->beta2 >= 0.0 && hp->beta2 < 1.0)) return fail(ECO_EINVAL, "beta2 must lie in [0, 1)");
     if (!std::isfinite(hp->eps) || hp->eps < 0.0) return fail(ECO_EINVAL, "eps must be finite and >= 0");
   }
+  // valid doubles can still leave the fp32 range once combined (a tiny lr makes the injection strength
+  // (1/lr)(1 - 1/beta) overflow): the step would then write non-finite state
+  eco_constants_t c;
+  derive_constants(hp, &c);
+  const float all[] = {c.b1, c.omb1, c.b2, c.omb2, c.rbc2, c.c1, c.eps, c.kappa, c.lr, c.alpha, c.wd, c.inv_lr, c.inv_lr_beta};
+  for (float x : all)
+    if (!std::isfinite(x)) return fail(ECO_EINVAL, "a step constant derived from lr, the betas and the step index is not finite in fp32");
   return ECO_OK;
 }
 
@@ -141,8 +152,9 @@ uint32_t lds_for_waves(int waves, int granule) {
 // measured 10-15 % slower on MI355X.  Option 0 overrides with a resident grid.
 unsigned grid_for(uint64_t tiles, int cus) {
   uint64_t g = tiles;
-  if (g_wgs_per_cu > 0) {
-    const uint64_t cap = static_cast<uint64_t>(cus) * static_cast<uint64_t>(g_wgs_per_cu);
+  const int64_t wgs_per_cu = g_wgs_per_cu.load(std::memory_order_relaxed);
+  if (wgs_per_cu > 0) {
+    const uint64_t cap = static_cast<uint64_t>(cus) * static_cast<uint64_t>(wgs_per_cu);
     if (g > cap) g = cap;
   }
   if (g > 0x7FFFFFFFull) g = 0x7FFFFFFFull;
@@ -176,7 +188,7 @@ const char *eco_status_string(eco_status_t s) {
 
 const char *eco_last_error(void) { return g_last_error.c_str(); }
 
-int eco_version(void) { return 100; }
+int eco_version(void) { return 200; }
 
 eco_status_t eco_set_option(int32_t option, int64_t value) {
   if (option == 0) {
@@ -361,6 +373,7 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev != plan->device)
     return fail(ECO_EINVAL, "step: the plan was created on device %d, which is not the current device (%d)", plan->device, dev);
+  (void)hipGetLastError();   // an error left behind by the caller's earlier HIP work is not this call's
 
   eco_constants_t c;
   derive_constants(hp, &c);
@@ -401,10 +414,11 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     kv.round = hp->round;
     const int waves = default_waves(kv);
     const int waves_wide = kv.algo == eco::ALGO_ADAM ? waves : 0;     // measured for Adam only; SGDM ran best uncapped
-    a.lds_bytes = g_lds_bytes >= 0 ? static_cast<uint32_t>(g_lds_bytes) : lds_for_waves(waves, 512);
-    a.lds_bytes_wave = g_lds_bytes_wave >= 0 ? static_cast<uint32_t>(g_lds_bytes_wave) : lds_for_waves(waves_wide, 256);
-    a.lds_bytes_tw = g_lds_bytes_wave >= 0 ? static_cast<uint32_t>(g_lds_bytes_wave)
-                                           : lds_for_waves(waves_wide ? waves_wide + 3 : 0, 256);
+    const int64_t opt_lds = g_lds_bytes.load(std::memory_order_relaxed);
+    const int64_t opt_lds_wave = g_lds_bytes_wave.load(std::memory_order_relaxed);
+    a.lds_bytes = opt_lds >= 0 ? static_cast<uint32_t>(opt_lds) : lds_for_waves(waves, 512);
+    a.lds_bytes_wave = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide, 256);
+    a.lds_bytes_tw = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide ? waves_wide + 3 : 0, 256);
     const hipError_t e = eco::launch_step(kv, a, grid_for(a.num_tiles, plan->cus), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "step kernel launch");
   }
@@ -447,6 +461,7 @@ eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t nume
   if (eco::classify_group(group_size, numel) == eco::GROUP_UNSUPPORTED)
     return fail(ECO_EUNSUPPORTED, "scale group of %llu elements: supported are powers of two in [32, 512], multiples of 8 "
                 "up to 8192, and the whole tensor", (unsigned long long)group_size);
+  (void)hipGetLastError();
   const hipError_t e = eco::launch_quantize_init(src, src_dtype == ECO_DT_BF16, numel, fmt, group_size,
                                                  scale_dtype == ECO_DT_BF16, weights, scales, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ECO_OK : fail_hip(e, "quantize kernel launch");
@@ -460,9 +475,25 @@ eco_status_t eco_dequantize(const void *weights, const void *scales, uint64_t nu
   if (!aligned16(dst)) return fail(ECO_EALIGN, "destination must be 16-byte aligned");
   if (group_size < 8 && group_size < numel)      // a single group over a tiny tensor is fine
     return fail(ECO_EUNSUPPORTED, "scale groups of fewer than 8 elements are not supported");
-  const hipError_t e = eco::launch_dequantize(weights, scales, numel, fmt, group_size, scale_dtype == ECO_DT_BF16, dst,
-                                              static_cast<hipStream_t>(stream));
+  (void)hipGetLastError();
+  const hipError_t e = eco::launch_dequantize(weights, scales, numel, fmt, group_size, scale_dtype == ECO_DT_BF16, nullptr, 0,
+                                              dst, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ECO_OK : fail_hip(e, "dequantize kernel launch");
+}
+
+eco_status_t eco_quantize_error(const void *src, int32_t src_dtype, const void *weights, const void *scales, uint64_t numel,
+                                int32_t fmt, uint64_t group_size, int32_t scale_dtype, float *err, void *stream) {
+  eco_status_t st = check_flat(weights, scales, numel, fmt, group_size, scale_dtype);
+  if (st != ECO_OK) return st;
+  if (!src || !err) return fail(ECO_EINVAL, "null source or destination");
+  if (!is_dtype(src_dtype)) return fail(ECO_EINVAL, "unknown source dtype");
+  if (!aligned16(src) || !aligned16(err)) return fail(ECO_EALIGN, "source and destination must be 16-byte aligned");
+  if (group_size < 8 && group_size < numel)
+    return fail(ECO_EUNSUPPORTED, "scale groups of fewer than 8 elements are not supported");
+  (void)hipGetLastError();
+  const hipError_t e = eco::launch_dequantize(weights, scales, numel, fmt, group_size, scale_dtype == ECO_DT_BF16, src,
+                                              src_dtype == ECO_DT_BF16 ? 2 : 1, err, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ECO_OK : fail_hip(e, "quantization-error kernel launch");
 }
 
 eco_status_t eco_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_word, uint64_t n_words,
@@ -470,6 +501,7 @@ eco_status_t eco_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, u
   if (!dst) return fail(ECO_EINVAL, "null destination");
   if (n_words == 0) return fail(ECO_EINVAL, "n_words == 0");
   if (first_word + n_words < first_word) return fail(ECO_EINVAL, "word range overflows");
+  (void)hipGetLastError();
   const hipError_t e = eco::launch_philox_fill(seed, step, tensor_id, first_word, n_words, dst, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ECO_OK : fail_hip(e, "philox kernel launch");
 }

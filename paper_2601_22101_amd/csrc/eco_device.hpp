@@ -63,7 +63,15 @@ constexpr uint32_t SQRT_MID_HI = 0x6F800000u;   // 2^96
 // bit pattern above 2^-6 (three mantissa bits kept, twenty dropped) and linear in the value
 // below it (spacing 2^-9), where the fp32 addition of 2^-6 performs the round-to-nearest-even
 // onto multiples of 2^-29.
+//
+// Stochastic rounding (Sec. 3.1: up with a probability proportional to the distance from the lower
+// neighbour, an unbiased estimator): with F the 20-bit fraction of the axis position and r the
+// element's 16 random bits, the code goes up iff F + 16 r + 8 >= 2^20, i.e. with probability
+// floor((F + 8) / 16) / 2^16 -- the fraction rounded to the nearest multiple of 2^-16, so that the
+// 16-bit resolution has no preferred direction (Assumption 3.2 wants a zero-mean error).  The +8 is
+// folded into the constants below.  F = 0 never goes up: 8 + 16 * 65535 < 2^20.
 constexpr uint32_t E4M3_MIN_NORMAL_BITS = 0x3C800000u;     // fp32 bit pattern of 2^-6
+constexpr uint32_t SR_CENTRE = 8u;                         // half of the 2^4 fraction units one random unit is worth
 
 // Magnitude code (0..126) of |y|.  NORMAL_ONLY: the caller guarantees |y| >= 2^-6 (the common
 // case, decided once per wave).  ay must be non-negative.
@@ -72,9 +80,9 @@ __device__ __forceinline__ uint32_t e4m3_encode_mag(float ay, uint32_t r16) {
   const uint32_t b = f2u(ay);
   uint32_t mag;
   if (ROUND == ROUND_SR) {
-    uint32_t axis = b - 0x3C000000u;                        // code 8 <-> 0x3C800000
-    if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = f2u(ay + 0x1p-6f) - 0x3C800000u;
-    mag = (axis + (r16 << 4)) >> 20;                        // up iff frac20 + 16*r16 >= 2^20
+    uint32_t axis = b - (0x3C000000u - SR_CENTRE);          // code 8 <-> 0x3C800000
+    if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = f2u(ay + 0x1p-6f) - (0x3C800000u - SR_CENTRE);
+    mag = (axis + (r16 << 4)) >> 20;                        // up iff frac20 + 16*r16 + 8 >= 2^20
   } else {
     if (NORMAL_ONLY || b >= E4M3_MIN_NORMAL_BITS) {
       const uint32_t k = b - 0x3C000000u;
@@ -107,8 +115,8 @@ __device__ __forceinline__ uint32_t int4_encode(float y, uint32_t r16) {
   if (ROUND == ROUND_SR) {
     // ulp(8.0) = 2^-20: the addition rounds |y| to nearest-even multiples of 2^-20
     // (for |y| >= 8 the bit pattern keeps growing, so the result saturates below)
-    const uint32_t k = f2u(ay + 8.0f) - 0x41000000u;
-    mag = (k + (r16 << 4)) >> 20;
+    const uint32_t k = f2u(ay + 8.0f) - (0x41000000u - SR_CENTRE);
+    mag = (k + (r16 << 4)) >> 20;                           // up iff frac20 + 16*r16 + 8 >= 2^20
   } else {
     mag = f2u(ay + 0x1p23f) - 0x4B000000u;                  // ulp(2^23) = 1: exact nearest-even
   }

@@ -79,12 +79,12 @@ struct KernelVariant {
   int round;        // ROUND_*
 };
 
-// Each launcher enqueues one kernel on `stream` and returns hipGetLastError().
+// Each launcher enqueues its kernels on `stream`, checks every launch, and returns the first error.
 hipError_t launch_step(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream);
 hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, int fmt, uint64_t group_size,
                                 int scale_bf16, void *weights, void *scales, hipStream_t stream);
 hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint64_t group_size,
-                             int scale_bf16, float *dst, hipStream_t stream);
+                             int scale_bf16, const void *src, int src_kind, float *dst, hipStream_t stream);
 
 // Scale-group classes (how the abs-max of a group is reduced)
 enum : int { GROUP_BLOCK = 0, GROUP_WIDE = 1, GROUP_TENSOR = 2, GROUP_UNSUPPORTED = -1 };

@@ -1,6 +1,8 @@
 // Kernels beside the fused quantized step: the unquantized ("plain") optimizer step for bf16 /
 // fp32 weights, the round-to-nearest initial quantizer, the dequantizer, and the raw Philox
 // stream.  They share the tile geometry and the 8-element access helpers of the step kernel.
+#include <mutex>
+
 #include "eco_step_kernel.hpp"
 
 namespace eco {
@@ -58,9 +60,9 @@ hipError_t launch_step_plain(const KernelVariant &kv, const StepArgs &args, unsi
 #define ECO_LAUNCH(F, ST, AD)                                                                                  \
   do {                                                                                                         \
     if (args.num_tiles)                                                                                        \
-      hipLaunchKernelGGL((eco_plain_kernel<F, ST, AD>), dim3(grid), dim3(WG_THREADS), 0, stream, args);        \
+      ECO_LAUNCH_CHECKED((eco_plain_kernel<F, ST, AD>), dim3(grid), dim3(WG_THREADS), 0, stream, args);        \
     if (args.num_ragged)                                                                                       \
-      hipLaunchKernelGGL((eco_plain_ragged_kernel<F, ST, AD>), dim3(args.num_ragged), dim3(WG_THREADS), 0,     \
+      ECO_LAUNCH_CHECKED((eco_plain_ragged_kernel<F, ST, AD>), dim3(args.num_ragged), dim3(WG_THREADS), 0,     \
                          stream, args);                                                                        \
   } while (0)
   const int key = (kv.fmt == FMT_FP32_ID ? 4 : 0) | (kv.state_bf16 ? 2 : 0) | (algo_is_adam(kv.algo) ? 0 : 1);
@@ -75,7 +77,7 @@ hipError_t launch_step_plain(const KernelVariant &kv, const StepArgs &args, unsi
     default: ECO_LAUNCH(FMT_FP32_ID, true, false); break;
   }
 #undef ECO_LAUNCH
-  return hipGetLastError();
+  return hipSuccess;
 }
 
 hipError_t launch_step(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
@@ -87,15 +89,18 @@ hipError_t launch_step(const KernelVariant &kv, const StepArgs &args, unsigned g
 // ------------------------------------------------------------------------ initial quantizer
 // q(x) of Sec. 3.1 with nearest-even rounding over one flat tensor, for the three classes of scale
 // groups (in-wave blocks, one workgroup per wide group, one scale for the whole tensor in two passes).
-// The two-pass form keeps its abs-max in one file-scope slot, so calls that use it must not overlap.
-__device__ uint32_t g_quantize_slot = 0;
+// The two-pass form keeps its abs-max, between its kernels, in one of QUANT_SLOTS file-scope slots; the host
+// hands the slots out in turn and makes a call wait (on its own stream) for the previous user of its slot, so
+// calls on different streams never share a slot that is in use.
+constexpr int QUANT_SLOTS = 64;
+__device__ uint32_t g_quantize_slots[QUANT_SLOTS];     // zero at load; every call leaves its slot at zero again
 
 template <int FMT, bool SCALE_BF16, bool SRC_BF16, int ACC, int RED>
 __device__ __forceinline__ void quantize_lane(const void *src, void *weights, void *scales, uint64_t e0, int nvalid,
-                                              uint64_t sg, int shift, bool scale_writer) {
+                                              uint64_t sg, int shift, bool scale_writer, uint32_t slot = 0) {
   float x[8];
   load_state8<SRC_BF16, ACC>(src, e0, nvalid, x);
-  const float amax = group_absmax<RED>(absmax8(x), shift, &g_quantize_slot);
+  const float amax = group_absmax<RED>(absmax8(x), shift, &g_quantize_slots[slot]);
   if (RED == RED_ATOMIC) return;
   float s_new, inv;
   block_scale<FMT, SCALE_BF16>(amax, s_new, inv);
@@ -133,64 +138,95 @@ __global__ __launch_bounds__(1024) void eco_quantize_wide_kernel(const void *src
 
 template <int FMT, bool SCALE_BF16, bool SRC_BF16, int RED>
 __global__ __launch_bounds__(WG_THREADS) void eco_quantize_tensorwise_kernel(const void *src, uint64_t numel, void *weights,
-                                                                             void *scales) {
+                                                                             void *scales, uint32_t slot) {
   const uint64_t e0 = (uint64_t)blockIdx.x * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-  quantize_lane<FMT, SCALE_BF16, SRC_BF16, ACC_LANE, RED>(src, weights, scales, e0, valid_from(e0, numel), 0, 0, false);
+  quantize_lane<FMT, SCALE_BF16, SRC_BF16, ACC_LANE, RED>(src, weights, scales, e0, valid_from(e0, numel), 0, 0, false, slot);
 }
 
 template <int FMT, bool SCALE_BF16>
-__global__ void eco_quantize_tensorwise_scale_kernel(void *scales) {
+__global__ void eco_quantize_tensorwise_scale_kernel(void *scales, uint32_t slot) {
   float s_new, inv;
-  block_scale<FMT, SCALE_BF16>(u2f(g_quantize_slot), s_new, inv);
+  block_scale<FMT, SCALE_BF16>(u2f(g_quantize_slots[slot]), s_new, inv);
   if (SCALE_BF16) static_cast<uint16_t *>(scales)[0] = (uint16_t)(f2u(s_new) >> 16);
   else static_cast<float *>(scales)[0] = s_new;
-  g_quantize_slot = 0;
+  g_quantize_slots[slot] = 0;
 }
 
+// Hands out the abs-max slots of the two-pass quantizer.  A slot is free again once the scale kernel of its
+// last user has run; the event recorded behind that kernel is what the next user of the slot waits for.
+struct QuantSlotRing {
+  static constexpr int MAX_DEVICES = 32;
+  std::mutex mu;
+  unsigned next[MAX_DEVICES] = {0};
+  hipEvent_t done[MAX_DEVICES][QUANT_SLOTS] = {{nullptr}};
+};
+static QuantSlotRing g_quant_ring;
+
 template <int FMT, bool SC, bool SR>
-static void launch_quantize_t(const void *src, uint64_t numel, uint64_t group_size, void *weights, void *scales,
-                              hipStream_t stream) {
+static hipError_t launch_quantize_t(const void *src, uint64_t numel, uint64_t group_size, void *weights, void *scales,
+                                    hipStream_t stream) {
   const uint64_t tiles = (numel + TILE_ELEMS - 1) / TILE_ELEMS;
   const int cls = classify_group(group_size, numel);
   if (cls == GROUP_BLOCK) {
-    hipLaunchKernelGGL((eco_quantize_kernel<FMT, SC, SR>), dim3((unsigned)tiles), dim3(WG_THREADS), 0, stream, src, numel,
+    ECO_LAUNCH_CHECKED((eco_quantize_kernel<FMT, SC, SR>), dim3((unsigned)tiles), dim3(WG_THREADS), 0, stream, src, numel,
                        (uint32_t)log2_exact(group_size), weights, scales);
   } else if (cls == GROUP_WIDE) {
     const uint64_t g = group_size < numel ? group_size : numel;
     const unsigned nw = (unsigned)((g + TILE_ELEMS - 1) / TILE_ELEMS);
-    hipLaunchKernelGGL((eco_quantize_wide_kernel<FMT, SC, SR>), dim3((unsigned)((numel + g - 1) / g)), dim3(64 * nw), 0,
+    ECO_LAUNCH_CHECKED((eco_quantize_wide_kernel<FMT, SC, SR>), dim3((unsigned)((numel + g - 1) / g)), dim3(64 * nw), 0,
                        stream, src, numel, g, weights, scales);
   } else {
-    hipLaunchKernelGGL((eco_quantize_tensorwise_kernel<FMT, SC, SR, RED_ATOMIC>), dim3((unsigned)tiles), dim3(WG_THREADS), 0,
-                       stream, src, numel, weights, scales);
-    hipLaunchKernelGGL((eco_quantize_tensorwise_kernel<FMT, SC, SR, RED_SLOT>), dim3((unsigned)tiles), dim3(WG_THREADS), 0,
-                       stream, src, numel, weights, scales);
-    hipLaunchKernelGGL((eco_quantize_tensorwise_scale_kernel<FMT, SC>), dim3(1), dim3(1), 0, stream, scales);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= QuantSlotRing::MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_quant_ring.mu);
+    const uint32_t slot = g_quant_ring.next[dev]++ % QUANT_SLOTS;
+    hipEvent_t &done = g_quant_ring.done[dev][slot];
+    if (done) {
+      e = hipStreamWaitEvent(stream, done, 0);          // the slot's previous user, on whatever stream it ran
+      if (e != hipSuccess) return e;
+    } else {
+      e = hipEventCreateWithFlags(&done, hipEventDisableTiming);
+      if (e != hipSuccess) { done = nullptr; return e; }
+    }
+    ECO_LAUNCH_CHECKED((eco_quantize_tensorwise_kernel<FMT, SC, SR, RED_ATOMIC>), dim3((unsigned)tiles), dim3(WG_THREADS), 0,
+                       stream, src, numel, weights, scales, slot);
+    ECO_LAUNCH_CHECKED((eco_quantize_tensorwise_kernel<FMT, SC, SR, RED_SLOT>), dim3((unsigned)tiles), dim3(WG_THREADS), 0,
+                       stream, src, numel, weights, scales, slot);
+    ECO_LAUNCH_CHECKED((eco_quantize_tensorwise_scale_kernel<FMT, SC>), dim3(1), dim3(1), 0, stream, scales, slot);
+    e = hipEventRecord(done, stream);
+    if (e != hipSuccess) return e;
   }
+  return hipSuccess;
 }
 
 hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, int fmt, uint64_t group_size, int scale_bf16,
                                 void *weights, void *scales, hipStream_t stream) {
   const int key = (fmt == FMT_INT4 ? 4 : 0) | (scale_bf16 ? 2 : 0) | (src_bf16 ? 1 : 0);
   switch (key) {
-    case 0: launch_quantize_t<FMT_FP8, false, false>(src, numel, group_size, weights, scales, stream); break;
-    case 1: launch_quantize_t<FMT_FP8, false, true>(src, numel, group_size, weights, scales, stream); break;
-    case 2: launch_quantize_t<FMT_FP8, true, false>(src, numel, group_size, weights, scales, stream); break;
-    case 3: launch_quantize_t<FMT_FP8, true, true>(src, numel, group_size, weights, scales, stream); break;
-    case 4: launch_quantize_t<FMT_INT4, false, false>(src, numel, group_size, weights, scales, stream); break;
-    case 5: launch_quantize_t<FMT_INT4, false, true>(src, numel, group_size, weights, scales, stream); break;
-    case 6: launch_quantize_t<FMT_INT4, true, false>(src, numel, group_size, weights, scales, stream); break;
-    default: launch_quantize_t<FMT_INT4, true, true>(src, numel, group_size, weights, scales, stream); break;
+    case 0: return launch_quantize_t<FMT_FP8, false, false>(src, numel, group_size, weights, scales, stream);
+    case 1: return launch_quantize_t<FMT_FP8, false, true>(src, numel, group_size, weights, scales, stream);
+    case 2: return launch_quantize_t<FMT_FP8, true, false>(src, numel, group_size, weights, scales, stream);
+    case 3: return launch_quantize_t<FMT_FP8, true, true>(src, numel, group_size, weights, scales, stream);
+    case 4: return launch_quantize_t<FMT_INT4, false, false>(src, numel, group_size, weights, scales, stream);
+    case 5: return launch_quantize_t<FMT_INT4, false, true>(src, numel, group_size, weights, scales, stream);
+    case 6: return launch_quantize_t<FMT_INT4, true, false>(src, numel, group_size, weights, scales, stream);
+    default: return launch_quantize_t<FMT_INT4, true, true>(src, numel, group_size, weights, scales, stream);
   }
-  return hipGetLastError();
 }
 
-// ------------------------------------------------------------------------ dequantizer
-// dst[i] = dec(code_i) * scale[i / group_size]; a lane's 8 elements may straddle two groups when the
-// group size is not a multiple of 8, so the scale index is taken per element.
-template <int FMT, bool SCALE_BF16>
+// ------------------------------------------------------------------------ dequantizer, quantization error
+// SRC == 0: dst[i] = dec(code_i) * scale[i / group_size] (Sec. 3.1, x^ = s*y).
+// SRC == 1 / 2: dst[i] = src[i] - dec(code_i) * scale[i / group_size] for an fp32 / bf16 source: the
+// quantization error e = theta - q(theta) of the notation paragraph of Sec. 3.1 (one multiplication, one
+// subtraction, each rounded to fp32).
+// A lane's 8 elements may straddle two groups when the group size is not a multiple of 8, so the scale
+// index is taken per element.
+template <int FMT, bool SCALE_BF16, int SRC>
 __global__ __launch_bounds__(WG_THREADS) void eco_dequantize_kernel(const void *weights, const void *scales,
-                                                                    uint64_t numel, uint64_t group_size, float *dst) {
+                                                                    uint64_t numel, uint64_t group_size, const void *src,
+                                                                    float *dst) {
   const uint64_t e0 = (uint64_t)blockIdx.x * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
   const int nvalid = valid_from(e0, numel);
   if (nvalid == 0) return;
@@ -205,19 +241,31 @@ __global__ __launch_bounds__(WG_THREADS) void eco_dequantize_kernel(const void *
   x[4] = decode_elem<FMT, 4>(c); x[5] = decode_elem<FMT, 5>(c); x[6] = decode_elem<FMT, 6>(c); x[7] = decode_elem<FMT, 7>(c);
 #pragma unroll
   for (int j = 0; j < 8; ++j) x[j] *= ((uint64_t)j < boundary ? s0 : s1);
+  if (SRC != 0) {
+    float t[8];
+    load_state8<SRC == 2, ACC_LANE>(src, e0, nvalid, t);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = t[j] - x[j];
+  }
   store_f32x8<ACC_LANE>(dst + e0, nvalid, x);
 }
 
+// src_kind: 0 = no source (plain de-quantization), 1 = fp32 source, 2 = bf16 source (dst = src - q)
 hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint64_t group_size,
-                             int scale_bf16, float *dst, hipStream_t stream) {
+                             int scale_bf16, const void *src, int src_kind, float *dst, hipStream_t stream) {
   const unsigned tiles = (unsigned)((numel + TILE_ELEMS - 1) / TILE_ELEMS);
-#define ECO_LAUNCH(F, SC)                                                                                            \
-  hipLaunchKernelGGL((eco_dequantize_kernel<F, SC>), dim3(tiles), dim3(WG_THREADS), 0, stream, weights, scales, numel, \
-                     group_size, dst)
-  if (fmt == FMT_FP8) { if (scale_bf16) ECO_LAUNCH(FMT_FP8, true); else ECO_LAUNCH(FMT_FP8, false); }
-  else { if (scale_bf16) ECO_LAUNCH(FMT_INT4, true); else ECO_LAUNCH(FMT_INT4, false); }
+#define ECO_LAUNCH(F, SC, SK)                                                                                          \
+  ECO_LAUNCH_CHECKED((eco_dequantize_kernel<F, SC, SK>), dim3(tiles), dim3(WG_THREADS), 0, stream, weights, scales, numel, \
+                     group_size, src, dst)
+#define ECO_LAUNCH_SRC(F, SC)                                                                                          \
+  do {                                                                                                                 \
+    if (src_kind == 0) ECO_LAUNCH(F, SC, 0); else if (src_kind == 1) ECO_LAUNCH(F, SC, 1); else ECO_LAUNCH(F, SC, 2);  \
+  } while (0)
+  if (fmt == FMT_FP8) { if (scale_bf16) ECO_LAUNCH_SRC(FMT_FP8, true); else ECO_LAUNCH_SRC(FMT_FP8, false); }
+  else { if (scale_bf16) ECO_LAUNCH_SRC(FMT_INT4, true); else ECO_LAUNCH_SRC(FMT_INT4, false); }
+#undef ECO_LAUNCH_SRC
 #undef ECO_LAUNCH
-  return hipGetLastError();
+  return hipSuccess;
 }
 
 // ------------------------------------------------------------------------ raw Philox stream

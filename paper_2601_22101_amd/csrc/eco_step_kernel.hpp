@@ -500,55 +500,62 @@ __global__ __launch_bounds__(WG_THREADS) void eco_tensorwise_scale_kernel(const 
 
 inline unsigned lds_cap(unsigned bytes) { return bytes < 65536u ? bytes : 65536u; }   // per-workgroup request limit
 
-template <int FMT, bool STATE_BF16, bool SC, int RD>
-void launch_step_algos(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
-#define ECO_LAUNCH(AL)                                                                                            \
+// Every launch is followed by its own error check, so that a failed launch stops the sequence and is the
+// error that is reported.
+#define ECO_LAUNCH_CHECKED(kernel, grid, block, lds, stream, ...)                                                 \
   do {                                                                                                            \
-    if (args.num_tiles)                                                                                           \
-      hipLaunchKernelGGL((eco_step_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(grid), dim3(WG_THREADS),            \
-                         args.lds_bytes, stream, args);                                                           \
-    if (args.num_ragged)                                                                                          \
-      hipLaunchKernelGGL((eco_step_ragged_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_ragged),            \
-                         dim3(WG_THREADS), 0, stream, args);                                                      \
-    for (int nw = 1; nw <= MAX_WIDE_WAVES; ++nw) {                                                                \
-      if (!args.num_wide[nw]) continue;                                                                           \
-      StepArgs wa = args;                                                                                         \
-      wa.wide_tensor = args.wide_base + args.wide_offset[nw];                                                     \
-      hipLaunchKernelGGL((eco_step_wide_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_wide[nw]),            \
-                         dim3(64 * nw), lds_cap(args.lds_bytes_wave * nw), stream, wa);                           \
-    }                                                                                                             \
-    if (args.num_tw_tiles) {                                                                                      \
-      hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_TILE>),                     \
-                         dim3(args.num_tw_tiles), dim3(WG_THREADS), args.lds_bytes_tw, stream, args);             \
-      hipLaunchKernelGGL((eco_tensorwise_reduce_kernel<FMT>), dim3(args.num_tw_tensors), dim3(TW_REDUCE_THREADS), \
-                         0, stream, args);                                                                        \
-      hipLaunchKernelGGL((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_SLOT>),                     \
-                         dim3(args.num_tw_tiles), dim3(WG_THREADS), args.lds_bytes_tw, stream, args);             \
-      hipLaunchKernelGGL((eco_tensorwise_scale_kernel<FMT, SC>),                                                  \
-                         dim3((args.num_tw_tensors + WG_THREADS - 1) / WG_THREADS), dim3(WG_THREADS), 0, stream,  \
-                         args);                                                                                   \
-    }                                                                                                             \
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                            \
+    const hipError_t launch_err_ = hipGetLastError();                                                             \
+    if (launch_err_ != hipSuccess) return launch_err_;                                                            \
   } while (0)
-  switch (kv.algo) {
-    case ALGO_ADAM: ECO_LAUNCH(ALGO_ADAM); break;
-    case ALGO_SGDM: ECO_LAUNCH(ALGO_SGDM); break;
-    case ALGO_SGDM_EXACT: ECO_LAUNCH(ALGO_SGDM_EXACT); break;
-    case ALGO_ADAM_MASTER: ECO_LAUNCH(ALGO_ADAM_MASTER); break;
-    default: ECO_LAUNCH(ALGO_SGDM_MASTER); break;
+
+template <int FMT, bool STATE_BF16, bool SC, int RD, int AL>
+hipError_t launch_step_kernels(const StepArgs &args, unsigned grid, hipStream_t stream) {
+  if (args.num_tiles)
+    ECO_LAUNCH_CHECKED((eco_step_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(grid), dim3(WG_THREADS), args.lds_bytes, stream, args);
+  if (args.num_ragged)
+    ECO_LAUNCH_CHECKED((eco_step_ragged_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_ragged), dim3(WG_THREADS), 0,
+                       stream, args);
+  for (int nw = 1; nw <= MAX_WIDE_WAVES; ++nw) {
+    if (!args.num_wide[nw]) continue;
+    StepArgs wa = args;
+    wa.wide_tensor = args.wide_base + args.wide_offset[nw];
+    ECO_LAUNCH_CHECKED((eco_step_wide_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_wide[nw]), dim3(64 * nw),
+                       lds_cap(args.lds_bytes_wave * nw), stream, wa);
   }
-#undef ECO_LAUNCH
+  if (args.num_tw_tiles) {
+    ECO_LAUNCH_CHECKED((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_TILE>), dim3(args.num_tw_tiles),
+                       dim3(WG_THREADS), args.lds_bytes_tw, stream, args);
+    ECO_LAUNCH_CHECKED((eco_tensorwise_reduce_kernel<FMT>), dim3(args.num_tw_tensors), dim3(TW_REDUCE_THREADS), 0, stream,
+                       args);
+    ECO_LAUNCH_CHECKED((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_SLOT>), dim3(args.num_tw_tiles),
+                       dim3(WG_THREADS), args.lds_bytes_tw, stream, args);
+    ECO_LAUNCH_CHECKED((eco_tensorwise_scale_kernel<FMT, SC>), dim3((args.num_tw_tensors + WG_THREADS - 1) / WG_THREADS),
+                       dim3(WG_THREADS), 0, stream, args);
+  }
+  return hipSuccess;
+}
+
+template <int FMT, bool STATE_BF16, bool SC, int RD>
+hipError_t launch_step_algos(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
+  switch (kv.algo) {
+    case ALGO_ADAM: return launch_step_kernels<FMT, STATE_BF16, SC, RD, ALGO_ADAM>(args, grid, stream);
+    case ALGO_SGDM: return launch_step_kernels<FMT, STATE_BF16, SC, RD, ALGO_SGDM>(args, grid, stream);
+    case ALGO_SGDM_EXACT: return launch_step_kernels<FMT, STATE_BF16, SC, RD, ALGO_SGDM_EXACT>(args, grid, stream);
+    case ALGO_ADAM_MASTER: return launch_step_kernels<FMT, STATE_BF16, SC, RD, ALGO_ADAM_MASTER>(args, grid, stream);
+    default: return launch_step_kernels<FMT, STATE_BF16, SC, RD, ALGO_SGDM_MASTER>(args, grid, stream);
+  }
 }
 
 template <int FMT, bool STATE_BF16>
 hipError_t launch_step_variants(const KernelVariant &kv, const StepArgs &args, unsigned grid, hipStream_t stream) {
   const int key = (kv.scale_bf16 ? 2 : 0) | (kv.round == ROUND_RTN ? 1 : 0);
   switch (key) {
-    case 0: launch_step_algos<FMT, STATE_BF16, false, ROUND_SR>(kv, args, grid, stream); break;
-    case 1: launch_step_algos<FMT, STATE_BF16, false, ROUND_RTN>(kv, args, grid, stream); break;
-    case 2: launch_step_algos<FMT, STATE_BF16, true, ROUND_SR>(kv, args, grid, stream); break;
-    default: launch_step_algos<FMT, STATE_BF16, true, ROUND_RTN>(kv, args, grid, stream); break;
+    case 0: return launch_step_algos<FMT, STATE_BF16, false, ROUND_SR>(kv, args, grid, stream);
+    case 1: return launch_step_algos<FMT, STATE_BF16, false, ROUND_RTN>(kv, args, grid, stream);
+    case 2: return launch_step_algos<FMT, STATE_BF16, true, ROUND_SR>(kv, args, grid, stream);
+    default: return launch_step_algos<FMT, STATE_BF16, true, ROUND_RTN>(kv, args, grid, stream);
   }
-  return hipGetLastError();
 }
 
 }  // namespace eco

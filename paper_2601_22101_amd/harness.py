@@ -265,8 +265,8 @@ class DeviceWorkload:
                 if self.mode == eco.ECO_MODE_MASTER:
                     tv.aux.copy_(w)
                 elif self.mode == eco.ECO_MODE_EXACT:
-                    eco.eco_dequantize(tv.weights, tv.scales, tv.spec.numel, tv.fmt, gs, sdt, tv.aux)
-                    torch.sub(w, tv.aux, out=tv.aux)            # e_0 = theta_0 - q(theta_0)
+                    # e_0 = theta_0 - q(theta_0)
+                    eco.eco_quantize_error(w, eco.ECO_DT_FP32, tv.weights, tv.scales, tv.spec.numel, tv.fmt, gs, sdt, tv.aux)
             else:
                 tv.weights.copy_(w.to(torch.bfloat16))
             del w

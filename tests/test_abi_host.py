@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(eco):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(eco_[a-z_0-9]+)\s*\(", header))
     assert {"eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_quantize_init",
-            "eco_dequantize", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_status_string",
+            "eco_dequantize", "eco_quantize_error", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_status_string",
             "eco_last_error", "eco_version"} <= names
     for n in names:
         assert hasattr(eco.lib, n), n
@@ -124,6 +124,13 @@ def test_flat_helpers_validate(eco):
     assert q(bs=20, n=1 << 20) == eco.ECO_EUNSUPPORTED         # ... and are multiples of 8
     assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 1024, 0, 128, 0, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 100, 0, 7, 0, 0x3000, 0) == eco.ECO_EUNSUPPORTED
+    qe = lambda **kw: _status(eco, eco.eco_quantize_error, *[{**dict(src=0x1000, sd=0, w=0x2000, s=0x3000, n=1024, fmt=0, gs=128,
+                                                                     sc=0, err=0x4000, st=0), **kw}[k]
+                                                            for k in ("src", "sd", "w", "s", "n", "fmt", "gs", "sc", "err", "st")])
+    assert qe(src=None) == eco.ECO_EINVAL and qe(err=None) == eco.ECO_EINVAL and qe(w=None) == eco.ECO_EINVAL
+    assert qe(err=0x4004) == eco.ECO_EALIGN and qe(src=0x1008) == eco.ECO_EALIGN
+    assert qe(fmt=2) == eco.ECO_EINVAL and qe(sd=9) == eco.ECO_EINVAL and qe(n=0) == eco.ECO_EINVAL
+    assert qe(gs=4) == eco.ECO_EUNSUPPORTED
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 0, 0x1000, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_philox_fill, 1, 1, 0, 0, 16, None, 0) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_set_option, 5, 1) == eco.ECO_EINVAL
@@ -156,6 +163,12 @@ def test_step_constants_follow_the_paper(eco):
     assert _status(eco, eco.eco_step_constants, eco.make_hparams(mode=eco.ECO_MODE_EXACT)) == eco.ECO_EUNSUPPORTED
     c = eco.eco_step_constants(eco.make_hparams(mode=eco.ECO_MODE_MASTER))
     assert c.kappa == 0 and c.alpha == 0 and c.inv_lr == 0
+    # doubles that are valid one by one but leave the fp32 range once combined are refused: the injection strength
+    # (1/lr)(1 - 1/beta) of a tiny learning rate, the Adam step lr/(1-b1^k) of a huge one
+    assert _status(eco, eco.eco_step_constants, eco.make_hparams(lr=1e-42)) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_step_constants, eco.make_hparams(opt=eco.ECO_OPT_SGDM, lr=1e-40, beta1=0.5)) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_step_constants, eco.make_hparams(lr=1e39, inject=False)) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_step_constants, eco.make_hparams(lr=1e-30, inject=False)) == 0      # no division by lr without injection
 
 
 def test_product_package_never_reaches_the_oracle():

@@ -3,7 +3,9 @@ times (one plan over every tensor, default launch options).  The step is local t
 the oracle recomputes sampled spans of blocks one by one from the inputs the device had before the
 step: spans at the start, at a random interior block and at the end of a sample of tensors that
 always includes the first and last tensor, a router, the embedding and experts with all-zero
-gradients.  Properties that hold at any size are checked on the whole arena."""
+gradients -- and, in one step of every run, the first and the last span of EVERY quantized tensor, so
+that a wrong entry of the tile -> tensor tables cannot hide in a tensor that was not drawn.
+Properties that hold at any size are checked on the whole arena."""
 import numpy as np
 import pytest
 import torch
@@ -17,6 +19,7 @@ from gpu_util import ORACLE_FMT, bf16_bits, compare, oracle_step, step_config, t
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 SPAN_BLOCKS = 48          # 6144 elements: twelve 512-element tiles, not tile aligned in general
+EDGE_BLOCKS = 24          # spans of the every-tensor sweep: 3072 elements at each end of each tensor
 
 
 def pick_spans(wl, rng, n_tensors):
@@ -43,6 +46,22 @@ def pick_spans(wl, rng, n_tensors):
     return spans
 
 
+def edge_spans(wl):
+    """First and last span of every quantized tensor (one span when the tensor is short)."""
+    spans = []
+    for i, t in enumerate(wl.tensors):
+        if t.fmt not in ("fp8", "int4"):
+            continue
+        gs = t.group_size(wl.block_size)
+        ng = (t.numel + gs - 1) // gs
+        per = max(1, EDGE_BLOCKS * 128 // gs)
+        if gs >= t.numel and t.numel > 1 << 17:
+            continue              # one scale over a large tensor: the span would be the whole tensor (sampled instead)
+        for g0 in sorted({0, max(0, ng - per)}):
+            spans.append((i, g0, min(per, ng - g0)))
+    return spans
+
+
 def grab(tv, wl, g0, ngroups, with_aux=False):
     """Host copy of scale groups [g0, g0+ngroups) of one tensor."""
     gs = tv.spec.group_size(wl.block_size)
@@ -64,7 +83,7 @@ def all_finite(arena):
     return all(bool(torch.isfinite(c.float().sum())) for c in arena.split(1 << 28))
 
 
-def run_fullsize(wl, steps, n_tensors, seed, layout=None):
+def run_fullsize(wl, steps, n_tensors, seed, layout=None, every_tensor_step=2):
     from paper_2601_22101_amd import harness
     o32 = oracle.get("f32")
     rng = np.random.default_rng(seed)
@@ -75,6 +94,10 @@ def run_fullsize(wl, steps, n_tensors, seed, layout=None):
     for k in range(1, steps + 1):
         dw.fill_gradients(k)
         spans = pick_spans(wl, rng, n_tensors)
+        if k == min(every_tensor_step, steps):
+            have = {(i, g0) for i, g0, _ in spans}
+            spans += [sp for sp in edge_spans(wl) if (sp[0], sp[1]) not in have]
+        print(f"[fullsize] {wl.name} step {k}: {len(spans)} spans", flush=True)
         before = [grab(dw.tensors[i], wl, g0, n, with_aux) for i, g0, n in spans]
         hp = dw.hparams(k)
         dw.plan.step(hp)
@@ -110,23 +133,29 @@ def run_fullsize(wl, steps, n_tensors, seed, layout=None):
 
 def test_config3_gemma_shaped_sampled():
     n = run_fullsize(workloads.config3(), steps=5, n_tensors=10, seed=3)
-    assert n > 500_000
+    assert n > 1_500_000
 
 
 def test_config4_smoe_shaped_sampled():
     n = run_fullsize(workloads.config4(), steps=5, n_tensors=24, seed=4)
-    assert n > 1_000_000
+    assert n > 19_000_000          # 3 153 tensors x two spans of 3 072 elements, plus the sampled spans
 
 
 def test_config5_deepseek_shaped_int4_sampled():
     n = run_fullsize(workloads.config5(), steps=3, n_tensors=24, seed=5)
-    assert n > 1_000_000
+    assert n > 34_000_000          # 5 685 tensors x two spans
 
 
 def test_config4_row_wise_sampled():
     """One scale per row (Sec. 4.1): the wide-group kernel at full size; spans are whole rows."""
     n = run_fullsize(workloads.with_granularity(workloads.config4(), "row"), steps=3, n_tensors=16, seed=14)
     assert n > 300_000
+
+
+def test_config5_row_wise_int4_sampled():
+    """One scale per row on the INT4 / bf16-state set: the wide-group kernel with rows of 1408 and 2048 elements."""
+    n = run_fullsize(workloads.with_granularity(workloads.config5(), "row"), steps=2, n_tensors=16, seed=18)
+    assert n > 20_000_000
 
 
 def test_config4_tensor_wise_sampled():

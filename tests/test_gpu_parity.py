@@ -119,6 +119,34 @@ def test_randomized_quantize_and_dequantize(eco, o32, seed):
     eco.eco_dequantize(codes, scales, numel, fmt, gs, int(scale_bf16), out)
     ref = o32.dequantize(fmt, rc, rs, numel, min(gs, numel))
     assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), what
+    # the quantization error e = theta - q(theta) (Sec. 3.1 notation; the e_0 of Appendix A): one fp32 subtraction
+    err = torch.full((numel,), 7.0, dtype=torch.float32, device=DEV)
+    eco.eco_quantize_error(x.to(DEV), int(src_bf16), codes, scales, numel, fmt, gs, int(scale_bf16), err)
+    want = x.float().numpy() - ref
+    assert want.dtype == np.float32 and np.array_equal(err.cpu().numpy().view(np.uint32), want.view(np.uint32)), what
+
+
+def test_tensorwise_quantize_calls_may_overlap_on_two_streams(eco, o32):
+    """One scale per tensor needs the tensor's abs-max between two kernels of a call; calls on different streams
+    must not see each other's.  Many calls, alternating between two streams and more of them than the library
+    has slots, against the oracle."""
+    rng = np.random.default_rng(77)
+    streams = [torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)]
+    jobs = []
+    for k in range(150):
+        numel = int(rng.integers(9000, 400000))
+        fmt = int(rng.integers(0, 2))
+        x = torch.from_numpy((rng.standard_normal(numel) * 10.0 ** rng.uniform(-4, 1)).astype(np.float32))
+        jobs.append((numel, fmt, x, x.to(DEV), torch.zeros(numel if fmt == 0 else (numel + 1) // 2, dtype=torch.uint8, device=DEV),
+                     torch.zeros(1, dtype=torch.float32, device=DEV)))
+    torch.cuda.synchronize()
+    for k, (numel, fmt, x, xd, codes, scale) in enumerate(jobs):
+        eco.eco_quantize_init(xd, eco.ECO_DT_FP32, numel, fmt, numel, eco.ECO_DT_FP32, codes, scale, stream=streams[k & 1])
+    torch.cuda.synchronize()
+    for k, (numel, fmt, x, xd, codes, scale) in enumerate(jobs):
+        rc, rs = o32.quantize_rtn(fmt, x.numpy(), block_size=numel)
+        assert np.array_equal(codes.cpu().numpy(), rc), k
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), rs.view(np.uint32)), k
 
 
 # ---------------------------------------------------------------------------------- whole workloads

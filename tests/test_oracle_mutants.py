@@ -1,6 +1,6 @@
 """Are the oracle's pins strong enough?  Each case plants ONE plausible mistake (a dropped term, a wrong
 sign or index, a swapped operand, an off-by-one) in a copy of oracle/eco_oracle.c, builds it, and runs the
-pin tests (tests/test_oracle_{codec,random,step,modes}.py) against the copy in a child process: the pins must
+pin tests (tests/test_oracle_{codec,random,step,modes,bf16}.py) against the copy in a child process: the pins must
 fail.  The unmodified copy must pass.  Everything here runs on the CPU."""
 import os
 import shutil
@@ -13,7 +13,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "eco_oracle.c")
 PINS = ["tests/test_oracle_codec.py", "tests/test_oracle_random.py", "tests/test_oracle_step.py",
-        "tests/test_oracle_modes.py"]
+        "tests/test_oracle_modes.py", "tests/test_oracle_bf16.py"]
 
 # (name, text in the oracle, what a mistaken author might have written)
 MUTANTS = [
@@ -41,8 +41,10 @@ MUTANTS = [
     ("E4M3 exponent bias off by one", "ldexp((double)(8u + M), (int)E - 10)", "ldexp((double)(8u + M), (int)E - 9)"),
     ("E4M3 subnormal spacing", "ldexp((double)M, -9)", "ldexp((double)M, -10)"),
     ("nearest rounding: ties away from zero", "(below == above && (lo & 1))", "(below == above)"),
-    ("stochastic rounding: strict threshold", "up = (F + 16.0 * (double)r16 >= 1048576.0);", "up = (F + 16.0 * (double)r16 > 1048576.0);"),
-    ("stochastic rounding: random bits not scaled", "up = (F + 16.0 * (double)r16 >= 1048576.0);", "up = (F + (double)r16 >= 1048576.0);"),
+    ("stochastic rounding: strict threshold", "up = (F + 16.0 * (double)r16 + 8.0 >= 1048576.0);", "up = (F + 16.0 * (double)r16 + 8.0 > 1048576.0);"),
+    ("stochastic rounding: random bits not scaled", "up = (F + 16.0 * (double)r16 + 8.0 >= 1048576.0);", "up = (F + (double)r16 + 8.0 >= 1048576.0);"),
+    ("stochastic rounding: truncating rule (pulls toward zero)", "up = (F + 16.0 * (double)r16 + 8.0 >= 1048576.0);", "up = (F + 16.0 * (double)r16 >= 1048576.0);"),
+    ("stochastic rounding: rounds up where it should round down", "up = (F + 16.0 * (double)r16 + 8.0 >= 1048576.0);", "up = !(F + 16.0 * (double)r16 + 8.0 >= 1048576.0);"),
     ("INT4 nibbles transposed (read)", "return (i & 1) ? (unsigned)(codes[i >> 1] >> 4) : (unsigned)(codes[i >> 1] & 15u);",
      "return (i & 1) ? (unsigned)(codes[i >> 1] & 15u) : (unsigned)(codes[i >> 1] >> 4);"),
     ("INT4 negative codes not two's complement", "return (unsigned)(neg ? -mag : mag) & 15u;", "return (unsigned)(mag | (neg << 3)) & 15u;"),
@@ -57,6 +59,14 @@ MUTANTS = [
     ("exact injection: coefficients swapped", "mh = r_fma(-cb, e, r_fma(ca, aux[i], mt[j]));", "mh = r_fma(-ca, e, r_fma(cb, aux[i], mt[j]));"),
     ("master weights: update applied to the de-quantized weights", "if (mode == MODE_MASTER) w = aux[i];\n      else if (quantized)", "if (quantized)"),
     ("master weights: momentum gets the injection too", "else mh = mt[j];", "else mh = adam ? r_fma(kap * dd[j], e, mt[j]) : r_fma(alpha, e, mt[j]);"),
+    ("bf16 scales: codes relative to the unrounded scale", "if (scale_bf16) { s = bf16_round_(s); inv = (REAL)1 / s; }",
+     "if (scale_bf16) { s = bf16_round_(s); inv = (REAL)rho / a; }"),
+    ("bf16 state: denominator from the rounded second moment", "dd[j] = r_sqrt(vt * rbc2) + epsf;",
+     "dd[j] = r_sqrt((cfg->state_bf16 ? bf16_round_(vt) : vt) * rbc2) + epsf;"),
+    ("bf16 state: injection added onto the rounded first moment", "mh = adam ? r_fma(kap * dd[j], e, mt[j]) : r_fma(alpha, e, mt[j]);",
+     "mh = adam ? r_fma(kap * dd[j], e, cfg->state_bf16 ? bf16_round_(mt[j]) : mt[j]) : r_fma(alpha, e, cfg->state_bf16 ? bf16_round_(mt[j]) : mt[j]);"),
+    ("bf16 state: the momentum is stored unrounded", "m[i] = cfg->state_bf16 ? bf16_round_(mh) : mh;", "m[i] = mh;"),
+    ("error measured against the unrounded scale", "q = decode(fmt, code) * s_new;", "q = decode(fmt, code) / inv;"),
     ("old scale of the neighbouring block", "decode(fmt, get_code(fmt, codes, i)) * scales[b];", "decode(fmt, get_code(fmt, codes, i)) * scales[b > 0 ? b - 1 : 0];"),
 ]
 

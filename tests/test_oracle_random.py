@@ -101,9 +101,10 @@ def _neighbours(grid, ay):
 @pytest.mark.parametrize("fmt", [FMT_E4M3, FMT_INT4])
 def test_sr_exhaustive_over_random_field(o32, fmt):
     """For fixed y, sweep all 2^16 values of the element's random field: only the two neighbours
-    occur, and the number of 'up' outcomes is exactly floor(F / 16), F = f * 2^20 rounded to nearest even:
-    the probability of rounding up is proportional to the distance from the lower neighbour (Sec. 3.1) to
-    within 2^-16, and values whose F is a multiple of 16 (f = 1/2, 1/4, 1/16 below) hit it exactly."""
+    occur, and the number of 'up' outcomes is exactly floor((F + 8) / 16), F = f * 2^20 rounded to nearest
+    even: the probability of rounding up is the distance from the lower neighbour (Sec. 3.1) rounded to the
+    nearest multiple of 2^-16 -- within 2^-17 of it and in neither direction preferentially -- and values
+    whose F is a multiple of 16 (f = 1/2, 1/4, 1/16 below) hit it exactly."""
     table = o32.decode_table(fmt)
     grid = sorted(Fraction(float(v)) for v in (table[:127] if fmt == FMT_E4M3 else table[:8]))
     rho = grid[-1]
@@ -112,7 +113,12 @@ def test_sr_exhaustive_over_random_field(o32, fmt):
     ys += [np.float32(2.0 ** -12), np.float32(0.0123), np.float32(float(rho) - 1e-3), np.float32(1.0),
            np.float32(3.0 + 2.0 ** -20), np.float32(1.5 - 2.0 ** -20),
            np.float32(1.0625), np.float32(2.5), np.float32(3.25), np.float32(5.0625), np.float32(6.5)]
+    # fractions with every residue of F modulo 16 just above a grid point (1.0 is on both grids; the next
+    # grid point is 1.125 for E4M3 and 2 for INT4, so one unit of F is 2^-23 resp. 2^-20)
+    unit = 2.0 ** -23 if fmt == FMT_E4M3 else 2.0 ** -20
+    ys += [np.float32(1.0 + k * unit) for k in list(range(1, 34)) + [2 ** 20 - 9, 2 ** 20 - 8, 2 ** 20 - 1]]
     r = np.arange(65536, dtype=np.uint16)
+    seen_residues = set()
     for y in ys:
         for sign in (1, -1):
             codes = o32.encode(fmt, ROUND_SR, np.full(65536, sign * y, dtype=np.float32), r)
@@ -120,20 +126,39 @@ def test_sr_exhaustive_over_random_field(o32, fmt):
             j, lo, hi = _neighbours(grid, Fraction(float(y)))
             assert set(np.unique(vals)) <= {float(lo), float(hi)}
             f = (Fraction(float(y)) - lo) / (hi - lo)
+            F = round(f * 2 ** 20)                     # Python rounds exact halves to even, like the definition
+            seen_residues.add(F % 16)
             ups = int((vals == float(hi)).sum()) if hi != lo else 0
-            assert ups == round(f * 2 ** 20) // 16, (float(y), ups, float(f * 65536))
-            assert abs(ups - f * 65536) <= 1
+            assert ups == (F + 8) // 16, (float(y), ups, float(f * 65536))
+            assert abs(ups - f * 65536) <= Fraction(1, 2) + Fraction(1, 32)     # nearest multiple (F itself is rounded below 2^-6)
             if f == 0:
                 assert ups == 0
+            # the up outcomes are the LARGEST random fields: up iff F + 16 r + 8 >= 2^20
+            if 0 < ups < 65536:
+                assert np.all(vals[65536 - ups:] == float(hi)) and np.all(vals[:65536 - ups] == float(lo))
             # sign symmetry: the magnitude decision does not depend on the sign
             if sign == -1:
                 pos = o32.encode(fmt, ROUND_SR, np.full(65536, y, dtype=np.float32), r)
                 assert np.array_equal(np.abs(table[pos]), np.abs(table[codes]))
+    assert seen_residues == set(range(16))
+
+
+def test_sr_resolution_has_no_preferred_direction():
+    """The 16-bit resolution of the random field: P(up) - f, averaged over the 16 residues of F modulo 16, is
+    2^-21 of a grid step (a rule that truncates F/16 instead would pull every value toward zero by 15/32 of
+    2^-16, on every element at every step).  Stated for the rule itself, in exact rationals."""
+    for base in (0, 16, 4096, 2 ** 20 - 16):
+        bias = [Fraction((F + 8) // 16, 2 ** 16) - Fraction(F, 2 ** 20) for F in range(base, base + 16)]
+        assert abs(sum(bias) / 16) <= Fraction(1, 2 ** 21)
+        assert max(abs(b) for b in bias) <= Fraction(1, 2 ** 17)
+        trunc = [Fraction(F // 16, 2 ** 16) - Fraction(F, 2 ** 20) for F in range(base, base + 16)]
+        assert sum(trunc) / 16 == -Fraction(15, 2 ** 21)
 
 
 @pytest.mark.parametrize("fmt,rho", [(FMT_E4M3, 448.0), (FMT_INT4, 7.0)])
 def test_sr_unbiased_with_philox_bits(o32, fmt, rho):
-    """E[dec(SR(y))] = y, checked with the oracle's own Philox-driven random fields."""
+    """E[dec(SR(y))] = y (Sec. 3.1: stochastic rounding is an unbiased estimator; Assumption 3.2), checked with
+    the oracle's own Philox-driven random fields, on single values and on a spread of values."""
     table = o32.decode_table(fmt).astype(np.float64)
     n = 1 << 20
     r = o32.random16(2024, 3, 5, n)
@@ -143,5 +168,10 @@ def test_sr_unbiased_with_philox_bits(o32, fmt, rho):
         vals = table[codes]
         step = np.ptp(vals)                       # distance between the two neighbours
         assert step > 0
-        # standard error of a two-point variable is at most step/2/sqrt(n); allow 5 sigma + the 2^-16 resolution
-        assert abs(vals.mean() - float(y32)) <= 5 * step / 2 / np.sqrt(n) + step * 2.0 ** -16
+        # standard error of a two-point variable is at most step/2/sqrt(n); 5 sigma
+        assert abs(vals.mean() - float(y32)) <= 5 * step / 2 / np.sqrt(n)
+    # many different values inside one grid cell: the mean error over them is zero within 5 sigma as well
+    lo, hi = (1.0, 1.125) if fmt == FMT_E4M3 else (1.0, 2.0)
+    ys = np.random.default_rng(5).uniform(lo, hi, n).astype(np.float32)
+    err = table[o32.encode(fmt, ROUND_SR, ys, r)] - ys.astype(np.float64)
+    assert abs(err.mean()) <= 5 * (hi - lo) / 2 / np.sqrt(n)
