@@ -3,6 +3,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <atomic>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -162,6 +163,68 @@ unsigned grid_for(uint64_t tiles, int cus) {
   return static_cast<unsigned>(g);
 }
 
+// Validation of one tensor descriptor against the layout part of the hyper-parameters; on success *gsz is the
+// tensor's scale group and *cls its class (eco::GROUP_*).
+eco_status_t check_tensor(const eco_tensor_t &t, size_t i, const eco_hparams_t *layout, uint64_t *gsz, int *cls) {
+  const bool needs_aux = layout->mode == ECO_MODE_EXACT || layout->mode == ECO_MODE_MASTER;
+  if (t.fmt < ECO_FMT_FP8_E4M3 || t.fmt > ECO_FMT_FP32_IDENTITY) return fail(ECO_EINVAL, "tensor %zu: unknown format %d", i, t.fmt);
+  if (t.numel == 0) return fail(ECO_EINVAL, "tensor %zu: numel == 0", i);
+  const bool quantized = t.fmt == ECO_FMT_FP8_E4M3 || t.fmt == ECO_FMT_INT4;
+  if (!t.weights || !t.grad || !t.m) return fail(ECO_EINVAL, "tensor %zu: null weights, grad or m", i);
+  if (quantized && !t.scales) return fail(ECO_EINVAL, "tensor %zu: quantized format needs scales", i);
+  if (layout->opt == ECO_OPT_ADAM && !t.v) return fail(ECO_EINVAL, "tensor %zu: Adam needs v", i);
+  if (quantized && needs_aux && !t.aux) return fail(ECO_EINVAL, "tensor %zu: this mode needs the aux buffer", i);
+  if (!aligned16(t.weights) || !aligned16(t.grad) || !aligned16(t.m) || (quantized && !aligned16(t.scales)) ||
+      (layout->opt == ECO_OPT_ADAM && !aligned16(t.v)) || (quantized && needs_aux && !aligned16(t.aux)))
+    return fail(ECO_EALIGN, "tensor %zu: every data pointer must be 16-byte aligned", i);
+  *gsz = t.group_size ? t.group_size : layout->block_size;
+  *cls = quantized ? eco::classify_group(*gsz, t.numel) : eco::GROUP_BLOCK;
+  if (*cls == eco::GROUP_UNSUPPORTED)
+    return fail(ECO_EUNSUPPORTED, "tensor %zu: scale group of %llu elements: supported are powers of two in [32, 512], "
+                "multiples of 8 up to 8192, and the whole tensor", i, (unsigned long long)*gsz);
+  return ECO_OK;
+}
+
+// The layout part of the hyper-parameters (what eco_plan_create reads).
+eco_status_t check_layout(const eco_hparams_t *layout) {
+  if (!layout) return fail(ECO_EINVAL, "plan: null layout");
+  if (layout->opt != ECO_OPT_ADAM && layout->opt != ECO_OPT_SGDM) return fail(ECO_EINVAL, "opt %d: unknown optimizer", layout->opt);
+  if (!is_dtype(layout->state_dtype) || !is_dtype(layout->scale_dtype)) return fail(ECO_EINVAL, "unknown state or scale dtype");
+  if (layout->mode < ECO_MODE_NAIVE || layout->mode > ECO_MODE_MASTER) return fail(ECO_EINVAL, "mode %d: unknown mode", layout->mode);
+  if (layout->mode == ECO_MODE_EXACT && layout->opt != ECO_OPT_SGDM)
+    return fail(ECO_EUNSUPPORTED, "exact stored-error injection is defined for SGDM only");
+  return check_block_size(layout->block_size);
+}
+
+// The kernel variant of a step with these hyper-parameters on tensors of format f.
+eco::KernelVariant variant_for(const eco_hparams_t *hp, int f) {
+  eco::KernelVariant kv;
+  kv.fmt = f;
+  kv.state_bf16 = hp->state_dtype == ECO_DT_BF16;
+  kv.scale_bf16 = hp->scale_dtype == ECO_DT_BF16;
+  if (hp->mode == ECO_MODE_MASTER) kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM_MASTER : eco::ALGO_SGDM_MASTER;
+  else if (hp->mode == ECO_MODE_EXACT) kv.algo = eco::ALGO_SGDM_EXACT;
+  else kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM : eco::ALGO_SGDM;
+  kv.round = hp->round;
+  return kv;
+}
+
+// The scalar part of the kernel arguments: step constants, random-stream key, launch options.
+void fill_step_scalars(const eco_hparams_t *hp, const eco_constants_t &c, const eco::KernelVariant &kv, eco::StepArgs *a) {
+  a->b1 = c.b1; a->omb1 = c.omb1; a->b2 = c.b2; a->omb2 = c.omb2; a->rbc2 = c.rbc2; a->c1 = c.c1; a->eps = c.eps;
+  a->kappa = c.kappa; a->lr = c.lr; a->alpha = c.alpha; a->wd = c.wd; a->inv_lr = c.inv_lr; a->inv_lr_beta = c.inv_lr_beta;
+  a->seed_lo = static_cast<uint32_t>(hp->seed);
+  a->seed_hi = static_cast<uint32_t>(hp->seed >> 32);
+  a->step_lo = static_cast<uint32_t>(hp->step);
+  const int waves = default_waves(kv);
+  const int waves_wide = kv.algo == eco::ALGO_ADAM ? waves : 0;     // measured for Adam only; SGDM ran best uncapped
+  const int64_t opt_lds = g_lds_bytes.load(std::memory_order_relaxed);
+  const int64_t opt_lds_wave = g_lds_bytes_wave.load(std::memory_order_relaxed);
+  a->lds_bytes = opt_lds >= 0 ? static_cast<uint32_t>(opt_lds) : lds_for_waves(waves, 512);
+  a->lds_bytes_wave = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide, 256);
+  a->lds_bytes_tw = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide ? waves_wide + 3 : 0, 256);
+}
+
 }  // namespace
 
 struct eco_plan {
@@ -244,14 +307,7 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   if (!out) return fail(ECO_EINVAL, "plan: null output pointer");
   *out = nullptr;
   if (!tensors || n == 0) return fail(ECO_EINVAL, "plan: empty tensor list");
-  if (!layout) return fail(ECO_EINVAL, "plan: null layout");
-  if (layout->opt != ECO_OPT_ADAM && layout->opt != ECO_OPT_SGDM) return fail(ECO_EINVAL, "opt %d: unknown optimizer", layout->opt);
-  if (!is_dtype(layout->state_dtype) || !is_dtype(layout->scale_dtype)) return fail(ECO_EINVAL, "unknown state or scale dtype");
-  if (layout->mode < ECO_MODE_NAIVE || layout->mode > ECO_MODE_MASTER) return fail(ECO_EINVAL, "mode %d: unknown mode", layout->mode);
-  if (layout->mode == ECO_MODE_EXACT && layout->opt != ECO_OPT_SGDM)
-    return fail(ECO_EUNSUPPORTED, "exact stored-error injection is defined for SGDM only");
-  const bool needs_aux = layout->mode == ECO_MODE_EXACT || layout->mode == ECO_MODE_MASTER;
-  eco_status_t st = check_block_size(layout->block_size);
+  eco_status_t st = check_layout(layout);
   if (st != ECO_OK) return st;
 
   eco_plan *plan = new (std::nothrow) eco_plan;
@@ -265,25 +321,11 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
   try {
     for (size_t i = 0; i < n; ++i) {
       const eco_tensor_t &t = tensors[i];
-      if (t.fmt < ECO_FMT_FP8_E4M3 || t.fmt > ECO_FMT_FP32_IDENTITY) { st = fail(ECO_EINVAL, "tensor %zu: unknown format %d", i, t.fmt); break; }
-      if (t.numel == 0) { st = fail(ECO_EINVAL, "tensor %zu: numel == 0", i); break; }
+      uint64_t gsz = 0;
+      int cls = 0;
+      st = check_tensor(t, i, layout, &gsz, &cls);
+      if (st != ECO_OK) break;
       const bool quantized = t.fmt == ECO_FMT_FP8_E4M3 || t.fmt == ECO_FMT_INT4;
-      if (!t.weights || !t.grad || !t.m) { st = fail(ECO_EINVAL, "tensor %zu: null weights, grad or m", i); break; }
-      if (quantized && !t.scales) { st = fail(ECO_EINVAL, "tensor %zu: quantized format needs scales", i); break; }
-      if (layout->opt == ECO_OPT_ADAM && !t.v) { st = fail(ECO_EINVAL, "tensor %zu: Adam needs v", i); break; }
-      if (quantized && needs_aux && !t.aux) { st = fail(ECO_EINVAL, "tensor %zu: this mode needs the aux buffer", i); break; }
-      if (!aligned16(t.weights) || !aligned16(t.grad) || !aligned16(t.m) || (quantized && !aligned16(t.scales)) ||
-          (layout->opt == ECO_OPT_ADAM && !aligned16(t.v)) || (quantized && needs_aux && !aligned16(t.aux))) {
-        st = fail(ECO_EALIGN, "tensor %zu: every data pointer must be 16-byte aligned", i);
-        break;
-      }
-      const uint64_t gsz = t.group_size ? t.group_size : layout->block_size;
-      const int cls = quantized ? eco::classify_group(gsz, t.numel) : eco::GROUP_BLOCK;
-      if (cls == eco::GROUP_UNSUPPORTED) {
-        st = fail(ECO_EUNSUPPORTED, "tensor %zu: scale group of %llu elements: supported are powers of two in [32, 512], "
-                  "multiples of 8 up to 8192, and the whole tensor", i, (unsigned long long)gsz);
-        break;
-      }
       Group &g = plan->groups[t.fmt];
       eco::TensorDesc d;
       std::memset(&d, 0, sizeof d);
@@ -399,26 +441,8 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream) {
     a.tile_max = g.d_tile_max;
     a.num_tw_tiles = static_cast<uint32_t>(g.tw_tile_tensor.size());
     a.num_tw_tensors = static_cast<uint32_t>(g.tw_tensor.size());
-    a.b1 = c.b1; a.omb1 = c.omb1; a.b2 = c.b2; a.omb2 = c.omb2; a.rbc2 = c.rbc2; a.c1 = c.c1; a.eps = c.eps;
-    a.kappa = c.kappa; a.lr = c.lr; a.alpha = c.alpha; a.wd = c.wd; a.inv_lr = c.inv_lr; a.inv_lr_beta = c.inv_lr_beta;
-    a.seed_lo = static_cast<uint32_t>(hp->seed);
-    a.seed_hi = static_cast<uint32_t>(hp->seed >> 32);
-    a.step_lo = static_cast<uint32_t>(hp->step);
-    eco::KernelVariant kv;
-    kv.fmt = f;
-    kv.state_bf16 = hp->state_dtype == ECO_DT_BF16;
-    kv.scale_bf16 = hp->scale_dtype == ECO_DT_BF16;
-    if (hp->mode == ECO_MODE_MASTER) kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM_MASTER : eco::ALGO_SGDM_MASTER;
-    else if (hp->mode == ECO_MODE_EXACT) kv.algo = eco::ALGO_SGDM_EXACT;
-    else kv.algo = hp->opt == ECO_OPT_ADAM ? eco::ALGO_ADAM : eco::ALGO_SGDM;
-    kv.round = hp->round;
-    const int waves = default_waves(kv);
-    const int waves_wide = kv.algo == eco::ALGO_ADAM ? waves : 0;     // measured for Adam only; SGDM ran best uncapped
-    const int64_t opt_lds = g_lds_bytes.load(std::memory_order_relaxed);
-    const int64_t opt_lds_wave = g_lds_bytes_wave.load(std::memory_order_relaxed);
-    a.lds_bytes = opt_lds >= 0 ? static_cast<uint32_t>(opt_lds) : lds_for_waves(waves, 512);
-    a.lds_bytes_wave = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide, 256);
-    a.lds_bytes_tw = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide ? waves_wide + 3 : 0, 256);
+    const eco::KernelVariant kv = variant_for(hp, f);
+    fill_step_scalars(hp, c, kv, &a);
     const hipError_t e = eco::launch_step(kv, a, grid_for(a.num_tiles, plan->cus), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "step kernel launch");
   }
