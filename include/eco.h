@@ -183,6 +183,22 @@ eco_status_t eco_step(eco_plan_t *plan, const eco_hparams_t *hp, void *stream);
 eco_status_t eco_step_tensors(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *hp, void *stream);
 
 /*
+ * eco_step_tensors_noalloc — eco_step_tensors for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results bit for
+ * bit; asynchronous on `stream` (it does not wait for it, unlike eco_step_tensors).  Calls no hipMalloc, hipFree,
+ * host-to-device copy or other allocating routine: the tensor descriptors, the launch tables and the abs-max
+ * scratch of tensors with a single scale live in one static device array of 8.7 MB (8 732 672 bytes) per GPU,
+ * held until the process ends, and the tables are written by a kernel from descriptors passed as kernel arguments.
+ * Limits: at most 4096 tensors per call and at most 2^20 launch-table entries in total (one per 512 elements of a
+ * tensor, rounded up, plus one per tensor with a ragged tail or a single scale; one per scale group for groups
+ * wider than 512 elements) -- about 5.3e8 elements per call; beyond that ECO_EUNSUPPORTED, before anything is
+ * launched.  Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different
+ * streams, different host threads) race; calls on one stream, or ordered by events, are safe.  Nothing in the
+ * array has to start at zero: every entry a step reads is written earlier in the same call.
+ */
+eco_status_t eco_step_tensors_noalloc(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *hp, void *stream);
+
+/*
  * eco_quantize_init — q(x) of Sec. 3.1 with round-to-nearest-even, for setting up quantized weights.
  *   src    : device, numel values of src_dtype (ECO_DT_FP32 or ECO_DT_BF16)
  *   weights, scales : device outputs, laid out as in eco_tensor_t

@@ -56,13 +56,14 @@ def _load() -> C.CDLL:
     lib.eco_plan_destroy.argtypes = [vp]
     lib.eco_step.argtypes = [vp, C.POINTER(eco_hparams_t), vp]
     lib.eco_step_tensors.argtypes = [C.POINTER(eco_tensor_t), C.c_size_t, C.POINTER(eco_hparams_t), vp]
+    lib.eco_step_tensors_noalloc.argtypes = [C.POINTER(eco_tensor_t), C.c_size_t, C.POINTER(eco_hparams_t), vp]
     lib.eco_quantize_init.argtypes = [vp, i32, u64, i32, u64, i32, vp, vp, vp]
     lib.eco_dequantize.argtypes = [vp, vp, u64, i32, u64, i32, vp, vp]
     lib.eco_quantize_error.argtypes = [vp, i32, vp, vp, u64, i32, u64, i32, vp, vp]
     lib.eco_philox_fill.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     lib.eco_step_constants.argtypes = [C.POINTER(eco_hparams_t), C.POINTER(eco_constants_t)]
     lib.eco_set_option.argtypes = [i32, C.c_int64]
-    for name in ("eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_quantize_init",
+    for name in ("eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_step_tensors_noalloc", "eco_quantize_init",
                  "eco_dequantize", "eco_quantize_error", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_version"):
         getattr(lib, name).restype = C.c_int
     lib.eco_status_string.argtypes = [C.c_int]
@@ -153,6 +154,11 @@ def eco_step(plan: int, hp: eco_hparams_t, stream=None) -> None:
 def eco_step_tensors(tensors: Sequence[eco_tensor_t], hp: eco_hparams_t, stream=None) -> None:
     arr = (eco_tensor_t * len(tensors))(*tensors)
     _check(lib.eco_step_tensors(arr, len(tensors), C.byref(hp), _stream(stream)))
+
+
+def eco_step_tensors_noalloc(tensors: Sequence[eco_tensor_t], hp: eco_hparams_t, stream=None) -> None:
+    arr = (eco_tensor_t * len(tensors))(*tensors)
+    _check(lib.eco_step_tensors_noalloc(arr, len(tensors), C.byref(hp), _stream(stream)))
 
 
 def eco_quantize_init(src, src_dtype: int, numel: int, fmt: int, group_size: int, scale_dtype: int, weights, scales,

@@ -1,6 +1,6 @@
 // C ABI of the ECO library (see include/eco.h): argument validation, derivation of the fp32 step
 // constants, launch plans (device tables mapping tiles to tensors) and kernel dispatch.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <atomic>
 #include <atomic>
@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -224,6 +225,105 @@ void fill_step_scalars(const eco_hparams_t *hp, const eco_constants_t &c, const 
   a->lds_bytes_wave = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide, 256);
   a->lds_bytes_tw = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide ? waves_wide + 3 : 0, 256);
 }
+
+
+// ------------------------------------------------------------------------------------------------------------
+// eco_step_tensors_noalloc: the plan-less step for callers that cannot allocate.  What eco_step_tensors puts
+// into freshly allocated device memory -- the tensor descriptors, the tile -> tensor launch tables, and the
+// abs-max slots and per-tile maxima of tensor-wise scaling -- lives in one static device array here; the tables
+// are written by a small kernel from descriptors passed as kernel arguments, so nothing is copied from host
+// memory either.  Every call on a GPU shares that GPU's array: calls that overlap on one GPU race.
+namespace noalloc {
+
+constexpr uint32_t MAX_TENSORS = ECO_NOALLOC_MAX_TENSORS;
+constexpr uint32_t MAX_UNITS = ECO_NOALLOC_MAX_UNITS;
+constexpr size_t OFF_DESCS = 0;
+constexpr size_t OFF_TABLES = OFF_DESCS + sizeof(eco::TensorDesc) * MAX_TENSORS;       // launch lists, back to back
+constexpr size_t OFF_SLOTS = OFF_TABLES + sizeof(uint32_t) * MAX_UNITS;                // one per tensor-wise tensor
+constexpr size_t OFF_TILE_MAX = OFF_SLOTS + sizeof(uint32_t) * MAX_TENSORS;            // one per tensor-wise tile
+constexpr size_t SCRATCH_BYTES = OFF_TILE_MAX + sizeof(uint32_t) * MAX_UNITS;
+static_assert(OFF_TABLES % 256 == 0 && OFF_SLOTS % 256 == 0 && OFF_TILE_MAX % 256 == 0, "scratch sections stay aligned");
+
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+
+// The array's device address, per device: in host code the array's name is only a handle for
+// hipGetSymbolAddress, never an address a kernel could use.
+constexpr int MAX_DEVICES = 32;
+std::mutex g_mu;
+unsigned char *g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+eco_status_t scratch_for_current_device(unsigned char **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(ECO_EUNSUPPORTED, "device %d: only devices 0..%d are supported", dev, MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return ECO_OK;
+}
+
+// One launch of the table builder carries up to BUILD_CHUNK descriptors by value.
+constexpr int BUILD_CHUNK = 32;
+struct BuildArgs {
+  eco::TensorDesc desc[BUILD_CHUNK];
+  uint32_t list_pos[BUILD_CHUNK];    // index into the tables of the first of this tensor's `units` entries
+  uint32_t units[BUILD_CHUNK];       // entries (tiles or groups) the tensor adds to its launch list
+  uint32_t extra_pos[BUILD_CHUNK];   // index of one more entry (ragged-tail list, tensor-wise tensor list), or NO_ENTRY
+  uint32_t first_index;              // descriptor index of desc[0]
+  uint32_t count;
+  unsigned char *scratch;
+};
+constexpr uint32_t NO_ENTRY = 0xFFFFFFFFu;
+static_assert(sizeof(BuildArgs) <= 4096, "kernel arguments are limited to 4 KB");
+
+constexpr int BUILD_THREADS = 256, BUILD_BLOCKS_PER_TENSOR = 32;
+__global__ __launch_bounds__(BUILD_THREADS) void eco_noalloc_build_kernel(const BuildArgs a) {
+  const uint32_t k = blockIdx.x;
+  if (k >= a.count) return;
+  const uint32_t index = a.first_index + k;
+  uint32_t *tables = reinterpret_cast<uint32_t *>(a.scratch + OFF_TABLES);
+  if (blockIdx.y == 0 && threadIdx.x < sizeof(eco::TensorDesc) / sizeof(uint64_t)) {
+    const uint64_t *src = reinterpret_cast<const uint64_t *>(&a.desc[k]);
+    reinterpret_cast<uint64_t *>(a.scratch + OFF_DESCS)[(size_t)index * (sizeof(eco::TensorDesc) / sizeof(uint64_t)) + threadIdx.x] =
+        src[threadIdx.x];
+  }
+  if (blockIdx.y == 0 && threadIdx.x == 0 && a.extra_pos[k] != NO_ENTRY) tables[a.extra_pos[k]] = index;
+  const uint32_t pos = a.list_pos[k], n = a.units[k];
+  for (uint32_t i = blockIdx.y * BUILD_THREADS + threadIdx.x; i < n; i += BUILD_BLOCKS_PER_TENSOR * BUILD_THREADS)
+    tables[pos + i] = index;
+}
+
+// Launch lists of one storage format, in the order they are laid out in the tables.
+enum : int { L_TILE = 0, L_RAGGED = 1, L_WIDE1 = 2, L_TW_TILES = L_WIDE1 + eco::MAX_WIDE_WAVES, L_TW_TENSORS, L_COUNT };
+
+struct ListOf { int list; int extra; uint64_t units; uint64_t group; };
+// Which lists a tensor enters, and with how many entries (mirrors eco_plan_create).
+ListOf lists_of(const eco_tensor_t &t, uint64_t gsz, int cls) {
+  ListOf r = {L_TILE, -1, 0, 0};
+  if (cls == eco::GROUP_BLOCK) {
+    r.units = t.numel / eco::TILE_ELEMS;
+    if (t.numel % eco::TILE_ELEMS) r.extra = L_RAGGED;
+    r.group = gsz;
+  } else if (cls == eco::GROUP_WIDE) {
+    r.group = gsz < t.numel ? gsz : t.numel;
+    r.units = (t.numel + r.group - 1) / r.group;
+    r.list = L_WIDE1 + static_cast<int>((r.group + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS) - 1;
+  } else {
+    r.group = t.numel;
+    r.units = (t.numel + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS;
+    r.list = L_TW_TILES;
+    r.extra = L_TW_TENSORS;
+  }
+  return r;
+}
+
+}  // namespace noalloc
 
 }  // namespace
 
@@ -461,6 +561,122 @@ eco_status_t eco_step_tensors(const eco_tensor_t *tensors, size_t n, const eco_h
   if (st != ECO_OK) return st;
   if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
   return st2;
+}
+
+eco_status_t eco_step_tensors_noalloc(const eco_tensor_t *tensors, size_t n, const eco_hparams_t *hp, void *stream) {
+  using namespace noalloc;
+  eco_status_t st = check_hparams(hp);
+  if (st != ECO_OK) return st;
+  st = check_layout(hp);
+  if (st != ECO_OK) return st;
+  if (!tensors || n == 0) return fail(ECO_EINVAL, "step: empty tensor list");
+  if (n > MAX_TENSORS)
+    return fail(ECO_EUNSUPPORTED, "eco_step_tensors_noalloc: %zu tensors, the static scratch holds %u (use a plan)", n, MAX_TENSORS);
+
+  // pass 1: validate, count the entries of every launch list
+  uint64_t count[4][L_COUNT] = {{0}};
+  uint64_t total = 0;
+  for (size_t i = 0; i < n; ++i) {
+    uint64_t gsz = 0;
+    int cls = 0;
+    st = check_tensor(tensors[i], i, hp, &gsz, &cls);
+    if (st != ECO_OK) return st;
+    const ListOf lo = lists_of(tensors[i], gsz, cls);
+    if (lo.units > MAX_UNITS) return fail(ECO_EUNSUPPORTED, "eco_step_tensors_noalloc: tensor %zu alone exceeds the static scratch", i);
+    count[tensors[i].fmt][lo.list] += lo.units;
+    if (lo.extra >= 0) count[tensors[i].fmt][lo.extra] += 1;
+    total += lo.units + (lo.extra >= 0 ? 1 : 0);
+    if (total > MAX_UNITS)
+      return fail(ECO_EUNSUPPORTED, "eco_step_tensors_noalloc: more than %u launch-table entries (512-element tiles, or scale "
+                  "groups wider than 512): the static scratch does not hold them (use a plan)", MAX_UNITS);
+  }
+  uint32_t start[4][L_COUNT], tw_tile_start[4], tw_tensor_start[4];
+  {
+    uint32_t pos = 0, tw_tiles = 0, tw_tensors = 0;
+    for (int f = 0; f < 4; ++f) {
+      for (int l = 0; l < L_COUNT; ++l) { start[f][l] = pos; pos += static_cast<uint32_t>(count[f][l]); }
+      tw_tile_start[f] = tw_tiles; tw_tiles += static_cast<uint32_t>(count[f][L_TW_TILES]);
+      tw_tensor_start[f] = tw_tensors; tw_tensors += static_cast<uint32_t>(count[f][L_TW_TENSORS]);
+    }
+  }
+
+  unsigned char *sp = nullptr;
+  st = scratch_for_current_device(&sp);
+  if (st != ECO_OK) return st;
+  (void)hipGetLastError();
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+
+  // pass 2: descriptors and tables, BUILD_CHUNK tensors per launch of the builder
+  uint32_t fill[4][L_COUNT] = {{0}};
+  BuildArgs ba;
+  std::memset(&ba, 0, sizeof ba);
+  ba.scratch = sp;
+  for (size_t i = 0; i < n; ++i) {
+    const eco_tensor_t &t = tensors[i];
+    uint64_t gsz = 0;
+    int cls = 0;
+    (void)check_tensor(t, i, hp, &gsz, &cls);
+    const ListOf lo = lists_of(t, gsz, cls);
+    const uint32_t k = ba.count++;
+    if (k == 0) ba.first_index = static_cast<uint32_t>(i);
+    eco::TensorDesc &d = ba.desc[k];
+    std::memset(&d, 0, sizeof d);
+    d.w = t.weights; d.s = t.scales; d.g = t.grad; d.m = t.m; d.v = t.v; d.aux = t.aux;
+    d.numel = t.numel;
+    d.tensor_id = t.tensor_id;
+    const bool quantized = t.fmt == ECO_FMT_FP8_E4M3 || t.fmt == ECO_FMT_INT4;
+    d.group_size = (cls == eco::GROUP_BLOCK && !quantized) ? hp->block_size : lo.group;
+    if (cls == eco::GROUP_BLOCK) d.bs_shift = static_cast<uint32_t>(eco::log2_exact(d.group_size));
+    d.first_unit = fill[t.fmt][lo.list];
+    ba.list_pos[k] = start[t.fmt][lo.list] + fill[t.fmt][lo.list];
+    ba.units[k] = static_cast<uint32_t>(lo.units);
+    fill[t.fmt][lo.list] += static_cast<uint32_t>(lo.units);
+    ba.extra_pos[k] = NO_ENTRY;
+    if (lo.extra >= 0) {
+      if (lo.extra == L_TW_TENSORS) d.slot = fill[t.fmt][lo.extra];
+      ba.extra_pos[k] = start[t.fmt][lo.extra] + fill[t.fmt][lo.extra]++;
+    }
+    if (ba.count == BUILD_CHUNK || i + 1 == n) {
+      hipLaunchKernelGGL(eco_noalloc_build_kernel, dim3(ba.count, BUILD_BLOCKS_PER_TENSOR), dim3(BUILD_THREADS), 0, hs, ba);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return fail_hip(e, "table kernel launch");
+      ba.count = 0;
+    }
+  }
+
+  eco_constants_t c;
+  derive_constants(hp, &c);
+  const int cus = num_compute_units();
+  const eco::TensorDesc *descs = reinterpret_cast<const eco::TensorDesc *>(sp + OFF_DESCS);
+  uint32_t *tables = reinterpret_cast<uint32_t *>(sp + OFF_TABLES);
+  for (int f = 0; f < 4; ++f) {
+    uint64_t any = 0;
+    for (int l = 0; l < L_COUNT; ++l) any += count[f][l];
+    if (!any) continue;
+    eco::StepArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.tensors = descs;
+    a.tile_tensor = tables + start[f][L_TILE];
+    a.ragged_tensor = tables + start[f][L_RAGGED];
+    a.num_tiles = static_cast<uint32_t>(count[f][L_TILE]);
+    a.num_ragged = static_cast<uint32_t>(count[f][L_RAGGED]);
+    a.wide_base = tables;
+    for (int nw = 1; nw <= eco::MAX_WIDE_WAVES; ++nw) {
+      a.wide_offset[nw] = start[f][L_WIDE1 + nw - 1];
+      a.num_wide[nw] = static_cast<uint32_t>(count[f][L_WIDE1 + nw - 1]);
+    }
+    a.tw_tile_tensor = tables + start[f][L_TW_TILES];
+    a.tw_tensor = tables + start[f][L_TW_TENSORS];
+    a.slots = reinterpret_cast<uint32_t *>(sp + OFF_SLOTS) + tw_tensor_start[f];
+    a.tile_max = reinterpret_cast<uint32_t *>(sp + OFF_TILE_MAX) + tw_tile_start[f];
+    a.num_tw_tiles = static_cast<uint32_t>(count[f][L_TW_TILES]);
+    a.num_tw_tensors = static_cast<uint32_t>(count[f][L_TW_TENSORS]);
+    const eco::KernelVariant kv = variant_for(hp, f);
+    fill_step_scalars(hp, c, kv, &a);
+    const hipError_t e = eco::launch_step(kv, a, grid_for(a.num_tiles, cus), hs);
+    if (e != hipSuccess) return fail_hip(e, "step kernel launch");
+  }
+  return ECO_OK;
 }
 
 static eco_status_t check_flat(const void *weights, const void *scales, uint64_t numel, int32_t fmt, uint64_t group_size,

@@ -31,6 +31,11 @@ constexpr int TILE_ELEMS = WG_THREADS * ELEMS_PER_LANE;
 // state only: with bf16 state the step moves half the bytes and is bound by instruction issue.
 constexpr uint32_t DEFAULT_STEP_LDS_BYTES = 13312;
 
+// Limits of the allocation-free plan-less step (its tables live in a static device array): tensors per call,
+// and launch-table entries per call (one per 512-element tile; one per scale group for groups wider than that).
+#define ECO_NOALLOC_MAX_TENSORS 4096
+#define ECO_NOALLOC_MAX_UNITS (1u << 20)
+
 constexpr int MAX_WIDE_WAVES = 16;          // widest single-workgroup scale group: 16 waves * 512 = 8192 elements
 constexpr uint64_t MAX_WIDE_GROUP = 8192;
 

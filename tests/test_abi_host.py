@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(eco):
     header = open(os.path.join(ROOT, "include", "eco.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(eco_[a-z_0-9]+)\s*\(", header))
-    assert {"eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_quantize_init",
+    assert {"eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_step_tensors_noalloc", "eco_quantize_init",
             "eco_dequantize", "eco_quantize_error", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_status_string",
             "eco_last_error", "eco_version"} <= names
     for n in names:
@@ -92,6 +92,24 @@ def test_plan_validation_happens_before_any_device_work(eco):
     # SGDM does not need v
     st = _status(eco, eco.eco_plan_create, [_tensor(eco, v=None)], eco.make_hparams(opt=eco.ECO_OPT_SGDM))
     assert st in (eco.ECO_OK, eco.ECO_EHIP, eco.ECO_ENOMEM)      # passes validation; no GPU here -> HIP error
+
+
+def test_noalloc_step_refuses_what_its_static_scratch_cannot_hold(eco):
+    """Limits of the allocation-free plan-less step are checked on the host, before any device work."""
+    hp = eco.make_hparams()
+    t = _tensor(eco)
+    assert _status(eco, eco.eco_step_tensors_noalloc, [t] * 4097, hp, 0) == eco.ECO_EUNSUPPORTED
+    assert "4096" in eco.eco_last_error()
+    assert _status(eco, eco.eco_step_tensors_noalloc, [_tensor(eco, numel=(1 << 29) + 512)], hp, 0) == eco.ECO_EUNSUPPORTED
+    assert _status(eco, eco.eco_step_tensors_noalloc, [_tensor(eco, numel=1 << 28)] * 3, hp, 0) == eco.ECO_EUNSUPPORTED
+    # one scale group per table entry for groups wider than 512 elements
+    assert _status(eco, eco.eco_step_tensors_noalloc, [_tensor(eco, numel=(1 << 20) * 520 + 520, group_size=520)], hp, 0) == eco.ECO_EUNSUPPORTED
+    # and the usual validation comes first
+    assert _status(eco, eco.eco_step_tensors_noalloc, [_tensor(eco, m=None)], hp, 0) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_step_tensors_noalloc, [_tensor(eco, grad=0x3004)], hp, 0) == eco.ECO_EALIGN
+    assert _status(eco, eco.eco_step_tensors_noalloc, [t], eco.make_hparams(step=0), 0) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_step_tensors_noalloc, [t], eco.make_hparams(block_size=100), 0) == eco.ECO_EUNSUPPORTED
+    assert _status(eco, eco.eco_step_tensors_noalloc, [], hp, 0) == eco.ECO_EINVAL
 
 
 def test_hparams_validation(eco):
