@@ -58,20 +58,40 @@ def algorithmic_bytes(wl, variant: str = "adam-sr") -> float:
     return total
 
 
+def kernel_source_hash() -> str:
+    """sha256 over the library's kernel and launch sources: what a committed profile was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2601_22101_amd", "csrc")
+    for fn in sorted(os.listdir(d)):
+        if fn.endswith((".hip", ".hpp", ".cpp")):
+            h.update(fn.encode())
+            h.update(open(os.path.join(d, fn), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def profiled_traffic(wl_name: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy of known
-    size) for this workload, as recorded in the committed profile summary; None if there is no such record."""
+    """HBM bytes per launch from the COMMITTED rocprofv3 --pmc summary of this workload (FETCH_SIZE / WRITE_SIZE scaled
+    by a copy of known size); it is not measured in this run.  Returns (bytes or None, where it comes from): None when
+    there is no record or when the record was taken on other kernel sources than the ones in the tree."""
     tag = {"cfg4_smoe_2p1b_shaped": "fp8_cfg4"}.get(wl_name)
     if not tag:
-        return None
-    path = os.path.join(ROOT, "profiles", f"eco_step_kernel_{tag}_hbm_traffic.txt")
+        return None, None
+    rel = os.path.join("profiles", f"eco_step_kernel_{tag}_hbm_traffic.txt")
+    val = src = None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch="):
-                return float(line.split("=", 1)[1])
+                val = float(line.split("=", 1)[1])
+            if line.startswith("kernel_source_sha256="):
+                src = line.split("=", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, None
+    if val is None:
+        return None, None
+    if src != kernel_source_hash():
+        return None, f"{rel} was taken on kernel sources {src}, the tree holds {kernel_source_hash()}: stale, not reported"
+    return val, f"replayed from {rel} (rocprofv3 --pmc on kernel sources {src}); not measured in this run"
 
 
 def static_bytes_per_param(wl, variant: str) -> float:
@@ -152,9 +172,124 @@ def cpu_baseline(wl, target_seconds: float = 10.0) -> dict:
         n1, dt1 = run(items, steps)
         n += n1
         dt += dt1
-    return {"value": n / dt, "unit": "params/s", "cores": o.num_threads(), "kind": "oracle",
+    threads = o.num_threads()
+    # the same oracle on one thread, on the first tensors of the sample (about two seconds of work)
+    o.set_threads(1)
+    sub, acc = [], 0
+    for it in items:
+        sub.append(it)
+        acc += it[1].numel
+        if acc >= 0.12 * rate * 16 / max(threads, 1):
+            break
+    n1t, dt1t = run(sub, steps + 1)
+    o.set_threads(threads)
+    return {"value": n / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "single_thread_value": n1t / dt1t, "cpu_model": cpu_model(),
             "sample": f"{steps} consecutive steps over the first {len(ids)} quantized tensors of the workload "
-                      f"({int(n1)} parameters each), fp32 build of the oracle, {dt:.1f} s"}
+                      f"({int(n1)} parameters each), fp32 build of the oracle, {dt:.1f} s; single thread: one step over "
+                      f"{int(n1t)} parameters, {dt1t:.1f} s"}
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def parity_step(dw, wl, step: int, gset: int, n_tensors: int = 40) -> dict:
+    """Part of the CPU-baseline leg: one more, untimed, step of the workload that was just timed, in the same launch
+    configuration; the oracle recomputes a seeded sample of block spans (start, interior, end of a sample of tensors that
+    includes the first and the last tensor, routers, the embedding) from the inputs the device held before the step, and
+    the device's results are compared with it element by element."""
+    import numpy as np
+    import torch
+
+    import oracle
+    o = oracle.get("f32")
+    fmt_map = {"fp8": oracle.FMT_E4M3, "int4": oracle.FMT_INT4}
+    rng = np.random.default_rng(workloads_seed() + step)
+    quant = [i for i, t in enumerate(wl.tensors) if t.fmt in fmt_map]
+    ids = {quant[0], quant[-1]} | {i for i in quant if "router" in wl.tensors[i].name or "embed" in wl.tensors[i].name}
+    ids = set(sorted(ids)[:8]) | {quant[-1]}
+    ids |= set(int(x) for x in rng.choice(quant, size=min(n_tensors, len(quant)), replace=False))
+    spans = []
+    for i in sorted(ids):
+        t = wl.tensors[i]
+        gs = t.group_size(wl.block_size)
+        ng = (t.numel + gs - 1) // gs
+        per = max(1, 48 * 128 // gs)
+        if gs >= t.numel and t.numel > 1 << 21:
+            continue
+        starts = {0, max(0, ng - per)}
+        if ng > 2 * per:
+            starts.add(int(rng.integers(1, ng - per)))
+        spans += [(i, g0, min(per, ng - g0)) for g0 in sorted(starts)]
+
+    def bits16(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16).copy()
+
+    def f32(t):
+        return oracle.bf16_bits_to_f32(bits16(t)) if t.dtype == torch.bfloat16 else t.cpu().numpy().astype(np.float32)
+
+    def grab(i, g0, n):
+        tv = dw.tensors[i]
+        gs = tv.spec.group_size(wl.block_size)
+        e0, e1 = g0 * gs, min((g0 + n) * gs, tv.spec.numel)
+        codes = tv.weights[e0:e1] if tv.spec.fmt == "fp8" else tv.weights[e0 // 2:(e1 + 1) // 2]
+        return dict(codes=codes.cpu().numpy().copy(), scales=f32(tv.scales[g0:g0 + n]), grad=bits16(dw.grad_view(tv, gset)[e0:e1]),
+                    m=f32(tv.m[e0:e1]), v=f32(tv.v[e0:e1])), e1 - e0
+
+    before = [grab(*sp) for sp in spans]
+    hp = dw.hparams(step)
+    dw.step(step, gset)
+    torch.cuda.synchronize()
+    out = {"elements": 0, "spans": len(spans), "tensors": len(ids), "code_mismatches": 0, "scale_mismatches": 0,
+           "m_max_rel": 0.0, "v_max_rel": 0.0, "m_bit_mismatches": 0, "v_bit_mismatches": 0}
+    for (i, g0, n), (h, numel) in zip(spans, before):
+        t = wl.tensors[i]
+        gs = t.group_size(wl.block_size)
+        cfg = oracle.StepConfig(fmt=fmt_map[t.fmt], opt=hp.opt, round=hp.round, mode=hp.mode, block_size=gs,
+                                state_bf16=wl.state_bf16, scale_bf16=wl.scale_bf16, lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2,
+                                eps=hp.eps, weight_decay=hp.weight_decay, step=hp.step, seed=hp.seed, elem_offset=g0 * gs,
+                                tensor_id=i)
+        assert o.eco_step(cfg, numel, h["m"], h["v"], codes=h["codes"], scales=h["scales"], grad_bf16=h["grad"]) == 0
+        got, _ = grab(i, g0, n)
+        out["elements"] += numel
+        out["code_mismatches"] += int((got["codes"] != h["codes"]).sum())
+        out["scale_mismatches"] += int((got["scales"].view(np.uint32) != h["scales"].view(np.uint32)).sum())
+        for key in ("m", "v"):
+            a, b = got[key].astype(np.float64), h[key].astype(np.float64)
+            rel = np.abs(a - b) / np.maximum(np.abs(b), 1e-30)
+            out[f"{key}_max_rel"] = max(out[f"{key}_max_rel"], float(rel.max()))
+            out[f"{key}_bit_mismatches"] += int((got[key].view(np.uint32) != h[key].view(np.uint32)).sum())
+    out["flip_rate"] = out["code_mismatches"] / max(out["elements"], 1)
+    out["what"] = (f"step {step} (one more step after the timed ones, same plan and launch configuration): the oracle recomputed "
+                   f"{len(spans)} spans of scale groups of {len(ids)} tensors from the device's inputs")
+    return out
+
+
+def workloads_seed() -> int:
+    import workloads
+    return workloads.BASE_SEED
+
+
+def time_launches(fn, reps: int, warm: int = 2):
+    """Average / median / min duration (ms) of `reps` calls of fn(), events on the current stream."""
+    import torch
+    for _ in range(warm):
+        fn()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    for i in range(reps):
+        ev[i].record()
+        fn()
+    ev[reps].record()
+    torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+    return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
 
 
 def main() -> int:
@@ -176,15 +311,21 @@ def main() -> int:
     ap.add_argument("--granularity", default="block", choices=["block", "row", "tensor"],
                     help="scale groups of the quantized tensors: the configuration's 128-element blocks (headline), "
                          "one scale per row (the paper's FP8 runs) or per tensor (its INT4 run)")
-    ap.add_argument("--placement", default="auto", choices=["auto", "packed", "spread"],
-                    help="where the harness puts the arenas in HBM: one allocation per arena (packed), or one allocation "
-                         "with the codes+gradient, m and v arenas tens of GiB apart (spread; auto = spread for workloads "
-                         "of 8 GiB and more): arrays streamed in lock-step are faster from different regions of HBM")
+    ap.add_argument("--placement", default="auto", choices=["auto", "packed", "spread", "dense", "dense-default"],
+                    help="where the harness puts the arenas in HBM: one allocation per arena (packed); one allocation without "
+                         "gaps, m first and v last with codes, scales and gradients between them (dense; auto = dense for "
+                         "workloads of 8 GiB and more) or in the order codes, scales, gradients, m, v (dense-default); one "
+                         "allocation with the codes+gradient, m and v arenas tens of GiB of unused memory apart (spread)")
     ap.add_argument("--spread-gap-gib", type=int, default=0, help="distance between the arena groups of the spread placement (0 = default)")
     ap.add_argument("--calibrate-gaps", type=int, default=3,
                     help="spread placement: time this many candidate distances (the default and smaller ones, 8 GiB apart) "
                          "in a probe at set-up and keep the fastest (0 or 1 = use the default distance)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true", help="skip the untimed parity step after the timed region")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the copy-kernel ceilings after the timed region")
+    ap.add_argument("--compare-placements", default="packed,spread",
+                    help="comma-separated placements to time the same step on after the headline run (configuration 4, "
+                         "headline variant only; empty = none)")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
                          "per tensor (same distribution; for runs under rocprofv3 --pmc)")
@@ -276,6 +417,8 @@ def main() -> int:
     avg_kernel_s = sum(kernel_ms) / len(kernel_ms) * 1e-3
     alg_bytes = algorithmic_bytes(wl, args.variant)
     achieved = alg_bytes / avg_kernel_s / 1e9
+    headline = args.variant == "adam-sr" and args.granularity == "block"
+    traffic, traffic_source = profiled_traffic(wl.name) if headline else (None, None)
     out = {
         "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -293,12 +436,53 @@ def main() -> int:
                                          "tensor": "two passes, a reduction and a scale kernel"}[args.granularity]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": profiled_traffic(wl.name) if args.variant == "adam-sr" and args.granularity == "block" else None,
-                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": avg_kernel_s * 1e3},
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": avg_kernel_s * 1e3,
+                     "kernel_ms_median": sorted(kernel_ms)[len(kernel_ms) // 2], "kernel_ms_min": min(kernel_ms)},
     }
+    quantized_only = all(t.fmt in ("fp8", "int4") for t in wl.tensors)
+    if not args.no_parity and not args.no_cpu_baseline and "master" not in args.variant and "exact" not in args.variant:
+        out["parity"] = parity_step(dw, wl, k + 1, k % grad_sets)
+        print(f"[bench] parity: {out['parity']}", file=sys.stderr, flush=True)
+    if not args.no_ceiling and args.config in (3, 4) and quantized_only and args.granularity == "block":
+        # what the memory system gives the step's access pattern without its arithmetic, on the very arrays just stepped
+        # (their contents are scrambled by it: nothing reads them afterwards)
+        n = min(dw.m.numel(), dw.codes.numel()) // 1024 * 1024
+        mix = time_launches(lambda: eco.eco_bandwidth_probe(0, dw.codes, dw.scales, dw.grad, dw.m, dw.v, n), 5)
+        cpy = time_launches(lambda: eco.eco_bandwidth_probe(1, None, None, None, dw.m, dw.v, n), 5)
+        out["roofline"]["ceiling_gbs"] = n * 20.0625 / (mix[0] * 1e-3) / 1e9
+        out["roofline"]["plain_copy_gbs"] = n * 8.0 / (cpy[0] * 1e-3) / 1e9
+        out["roofline"]["ceiling_what"] = ("eco_bandwidth_probe on the same arrays: ceiling_gbs = the step's loads and stores "
+                                           "(11.03 B read, 9.03 B written per element, same tiles and occupancy cap) without "
+                                           "arithmetic; plain_copy_gbs = float4 copy m -> v; averages of 5 launches")
+    placement_used = dw.placement
     dw.close()
     del dw
     torch.cuda.empty_cache()
+    others = [p for p in args.compare_placements.split(",") if p] if headline and args.config == 4 else []
+    for other in others:
+        dw2 = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk", placement=other, grad_sets=min(grad_sets, 4),
+                                     calibrate_gaps=0)
+        if dw2.placement == placement_used:
+            dw2.close()
+            continue
+        for g in range(len(dw2.grads)):
+            dw2.fill_gradients_bulk(g + 1, g)
+        torch.cuda.synchronize()
+        kk = [0]
+
+        def one():
+            kk[0] += 1
+            dw2.step(kk[0], (kk[0] - 1) % len(dw2.grads))
+        avg, med, mn = time_launches(one, args.steps, warm=args.warmup)
+        out.setdefault("other_placements", []).append(
+            {"placement": dw2.placement, "kernel_ms": avg, "kernel_ms_median": med, "kernel_ms_min": mn,
+             "frac": alg_bytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+             "what": f"the same step, {args.warmup} warm-up + {args.steps} timed launches, arbitrary valid weights"})
+        print(f"[bench] placement {dw2.placement}: {avg:.3f} ms", file=sys.stderr, flush=True)
+        dw2.close()
+        del dw2
+        torch.cuda.empty_cache()
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)

@@ -14,7 +14,8 @@
  *     theta^  = dec(code) * scale                         (Sec. 3.1, x^ = s*y)
  *     m~ = b1*m + (1-b1)*g ;  v~ = b2*v + (1-b2)*g*g      (Sec. 3.2 / Eq. m_tilde)
  *     d  = sqrt(v~/(1-b2^k)) + eps
- *     theta~ = theta^ - (lr/(1-b1^k)) * m~ / d            (Sec. 3.2, Adam display eq.)
+ *     eta_t = (lr/(1-b1^k)) / d ;  theta~ = theta^ - eta_t * m~
+ *                                                         (Sec. 3.2: element-wise step size eta_t)
  *     scale' = max|theta~| / rho ;  code' = round(theta~ * rho/max|theta~|)
  *                                                         (Sec. 3.1, Eq. 1 and s = max|x|/rho)
  *     e  = theta~ - dec(code')*scale'                     (Alg. 3 line 2)
@@ -236,6 +237,31 @@ eco_status_t eco_quantize_error(const void *src, int32_t src_dtype, const void *
  */
 eco_status_t eco_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_word, uint64_t n_words,
                              uint32_t *dst, void *stream);
+
+/*
+ * eco_bandwidth_probe — measurement aid, not part of the method: what the memory system delivers for the step's
+ * access pattern with the arithmetic taken out (the ceiling a step can be compared with).
+ *   kind 0: byte-mix copy.  Every lane loads what a lane of the FP8 / fp32-state Adam step loads for its 8 elements
+ *           (codes, gradient, m, v, the 128-block's scale) and stores what it stores, same tile geometry and
+ *           occupancy cap: 11.03 B read + 9.03 B written per element.  codes: numel bytes, scales: numel/128 fp32,
+ *           grad: numel bf16, m and v: numel fp32.  The contents of codes, m and v are scrambled (m and v swap).
+ *   kind 1: plain copy of numel fp32 from m to v (4 B read + 4 B written per element); the other pointers are ignored.
+ * numel: a multiple of 1024.  All pointers device, 16-byte aligned.  Asynchronous.
+ */
+eco_status_t eco_bandwidth_probe(int32_t kind, void *codes, void *scales, const void *grad, void *m, void *v, uint64_t numel,
+                                 void *stream);
+
+/*
+ * eco_arith_selftest — device self-test of the two short arithmetic sequences of the step kernels.  Inside stated
+ * operand ranges the kernels compute the correctly rounded square root (kind 0; arguments in [2^-96, 2^96]) and
+ * the correctly rounded quotient numerator / d (kind 1; |numerator| in [2^-40, 2^40], d in [2^-48, 2^49]) with
+ * shorter instruction sequences than sqrtf() and `/`; this call compares short and long form for every fp32 bit
+ * pattern x (kind 0) or d (kind 1) of [bits_lo, bits_hi) and ADDS the number of patterns on which they differ
+ * (expected: 0) to *mismatches (device memory, uint64, 8-byte aligned, cleared by the caller).  Ranges outside
+ * the ones above: ECO_EINVAL.  Asynchronous.
+ */
+eco_status_t eco_arith_selftest(int32_t kind, float numerator, uint32_t bits_lo, uint32_t bits_hi, uint64_t *mismatches,
+                                void *stream);
 
 /* eco_step_constants — host only: validates hp as eco_step does and writes the derived fp32 constants. */
 eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out);

@@ -14,7 +14,10 @@
  *     round = round-to-nearest or stochastic rounding.
  *   - Alg. 1: theta~, s~ <- OPTIM_STEP(theta^, s^, H); then ECO_QUANTIZE.
  *   - Sec. 3.2 "Adam" display equations: the Adam update written with the
- *     element-wise step size eta_t = eta / ((1-b1^t)(sqrt(v/(1-b2^t))+eps)).
+ *     element-wise step size eta_t = eta / ((1-b1^t)(sqrt(v/(1-b2^t))+eps));
+ *     the update is formed the way the section writes it, theta~ = theta^ -
+ *     eta_t (.) m~ with eta_t = (eta/(1-b1^t)) / (sqrt(v^)+eps) (one division,
+ *     one multiplication).
  *   - Alg. 3 (ECO_QUANTIZE for Adam):  m^ = m~ + ((1-b1^t)/eta)(1-1/b1) *
  *     (sqrt(v/(1-b2^t))+eps) (.) e ,  e = theta~ - q(theta~);  v is returned
  *     unchanged.
@@ -411,7 +414,7 @@ int oracle_eco_step(const oracle_cfg *cfg, uint64_t numel, uint8_t *codes, REAL 
       if (adam) {
         REAL vt = r_fma(b2, v[i], omb2 * (g * g));
         dd[j] = r_sqrt(vt * rbc2) + epsf;
-        u = (c1 * mt[j]) / dd[j];
+        u = (c1 / dd[j]) * mt[j];                        /* eta_t (.) m~: the element-wise step size of Sec. 3.2 */
         v[i] = cfg->state_bf16 ? bf16_round_(vt) : vt;   /* v is final after the gradient */
       } else {
         dd[j] = 0;

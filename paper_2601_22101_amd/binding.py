@@ -60,11 +60,13 @@ def _load() -> C.CDLL:
     lib.eco_quantize_init.argtypes = [vp, i32, u64, i32, u64, i32, vp, vp, vp]
     lib.eco_dequantize.argtypes = [vp, vp, u64, i32, u64, i32, vp, vp]
     lib.eco_quantize_error.argtypes = [vp, i32, vp, vp, u64, i32, u64, i32, vp, vp]
+    lib.eco_bandwidth_probe.argtypes = [i32, vp, vp, vp, vp, vp, u64, vp]
+    lib.eco_arith_selftest.argtypes = [i32, C.c_float, u32, u32, vp, vp]
     lib.eco_philox_fill.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     lib.eco_step_constants.argtypes = [C.POINTER(eco_hparams_t), C.POINTER(eco_constants_t)]
     lib.eco_set_option.argtypes = [i32, C.c_int64]
     for name in ("eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_step_tensors_noalloc", "eco_quantize_init",
-                 "eco_dequantize", "eco_quantize_error", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_version"):
+                 "eco_dequantize", "eco_quantize_error", "eco_bandwidth_probe", "eco_arith_selftest", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_version"):
         getattr(lib, name).restype = C.c_int
     lib.eco_status_string.argtypes = [C.c_int]
     lib.eco_status_string.restype = C.c_char_p
@@ -176,6 +178,14 @@ def eco_quantize_error(src, src_dtype: int, weights, scales, numel: int, fmt: in
                        stream=None) -> None:
     _check(lib.eco_quantize_error(_ptr(src), src_dtype, _ptr(weights), _ptr(scales), numel, fmt, group_size, scale_dtype,
                                   _ptr(err), _stream(stream)))
+
+
+def eco_bandwidth_probe(kind: int, codes, scales, grad, m, v, numel: int, stream=None) -> None:
+    _check(lib.eco_bandwidth_probe(kind, _ptr(codes), _ptr(scales), _ptr(grad), _ptr(m), _ptr(v), numel, _stream(stream)))
+
+
+def eco_arith_selftest(kind: int, numerator: float, bits_lo: int, bits_hi: int, mismatches, stream=None) -> None:
+    _check(lib.eco_arith_selftest(kind, numerator, bits_lo, bits_hi, _ptr(mismatches), _stream(stream)))
 
 
 def eco_philox_fill(seed: int, step: int, tensor_id: int, first_word: int, n_words: int, dst, stream=None) -> None:

@@ -217,6 +217,7 @@ void fill_step_scalars(const eco_hparams_t *hp, const eco_constants_t &c, const 
   a->seed_lo = static_cast<uint32_t>(hp->seed);
   a->seed_hi = static_cast<uint32_t>(hp->seed >> 32);
   a->step_lo = static_cast<uint32_t>(hp->step);
+  a->div_mid = (c.c1 >= 0x1p-40f && c.c1 <= 0x1p40f && c.eps <= 1.0f) ? 1u : 0u;
   const int waves = default_waves(kv);
   const int waves_wide = kv.algo == eco::ALGO_ADAM ? waves : 0;     // measured for Adam only; SGDM ran best uncapped
   const int64_t opt_lds = g_lds_bytes.load(std::memory_order_relaxed);
@@ -734,6 +735,39 @@ eco_status_t eco_quantize_error(const void *src, int32_t src_dtype, const void *
   const hipError_t e = eco::launch_dequantize(weights, scales, numel, fmt, group_size, scale_dtype == ECO_DT_BF16, src,
                                               src_dtype == ECO_DT_BF16 ? 2 : 1, err, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ECO_OK : fail_hip(e, "quantization-error kernel launch");
+}
+
+eco_status_t eco_bandwidth_probe(int32_t kind, void *codes, void *scales, const void *grad, void *m, void *v, uint64_t numel,
+                                 void *stream) {
+  if (kind != 0 && kind != 1) return fail(ECO_EINVAL, "probe kind %d: 0 = byte-mix copy, 1 = plain copy", kind);
+  if (!m || !v || (kind == 0 && (!codes || !scales || !grad))) return fail(ECO_EINVAL, "null array");
+  if (!aligned16(m) || !aligned16(v) || (kind == 0 && (!aligned16(codes) || !aligned16(scales) || !aligned16(grad))))
+    return fail(ECO_EALIGN, "every array must be 16-byte aligned");
+  if (numel == 0 || numel % 1024 != 0 || numel / eco::TILE_ELEMS > 0x7FFFFFFFull)
+    return fail(ECO_EINVAL, "numel must be a positive multiple of 1024 below 2^40");
+  eco::KernelVariant kv;
+  kv.fmt = eco::FMT_FP8; kv.state_bf16 = 0; kv.scale_bf16 = 0; kv.algo = eco::ALGO_ADAM; kv.round = eco::ROUND_SR;
+  const int64_t opt_lds = g_lds_bytes.load(std::memory_order_relaxed);
+  const uint32_t lds = opt_lds >= 0 ? static_cast<uint32_t>(opt_lds) : lds_for_waves(default_waves(kv), 512);
+  (void)hipGetLastError();
+  const hipError_t e = eco::launch_bandwidth_probe(kind, codes, scales, grad, m, v, numel, lds, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ECO_OK : fail_hip(e, "probe kernel launch");
+}
+
+eco_status_t eco_arith_selftest(int32_t kind, float numerator, uint32_t bits_lo, uint32_t bits_hi, uint64_t *mismatches,
+                                void *stream) {
+  if (kind != 0 && kind != 1) return fail(ECO_EINVAL, "self-test kind %d: 0 = square root, 1 = division", kind);
+  if (!mismatches || (reinterpret_cast<uintptr_t>(mismatches) & 7u)) return fail(ECO_EINVAL, "mismatch counter: null or not 8-byte aligned");
+  if (bits_hi <= bits_lo) return fail(ECO_EINVAL, "empty range of bit patterns");
+  // the ranges the short forms are used in (bit patterns of positive floats)
+  const uint32_t lo = kind == 0 ? 0x0F800000u : 0x27800000u, hi = kind == 0 ? 0x6F800001u : 0x58000001u;   // 2^-96..2^96 | 2^-48..2^49
+  if (bits_lo < lo || bits_hi > hi) return fail(ECO_EINVAL, "bit patterns outside the range the short form is used in");
+  if (kind == 1 && !(std::fabs(numerator) >= 0x1p-40f && std::fabs(numerator) <= 0x1p40f))
+    return fail(ECO_EINVAL, "numerator outside [2^-40, 2^40]");
+  (void)hipGetLastError();
+  const hipError_t e = eco::launch_arith_selftest(kind, numerator, bits_lo, bits_hi, reinterpret_cast<unsigned long long *>(mismatches),
+                                                  static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ECO_OK : fail_hip(e, "self-test kernel launch");
 }
 
 eco_status_t eco_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_word, uint64_t n_words,

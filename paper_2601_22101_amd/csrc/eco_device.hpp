@@ -59,6 +59,25 @@ __device__ __forceinline__ float sqrt_rn_midrange(float x) {
 constexpr uint32_t SQRT_MID_LO = 0x0F800000u;   // 2^-96
 constexpr uint32_t SQRT_MID_HI = 0x6F800000u;   // 2^96
 
+// Correctly rounded fp32 quotient n / d for 2^-40 <= |n| <= 2^40 and 2^-48 <= |d| <= 2^49.  It is the sequence
+// the compiler emits for `/` (reciprocal estimate, one Newton step on the reciprocal, the quotient, and two
+// residual corrections, every step a fused multiply-add) without its operand pre-scaling, post-scaling and
+// special-case fix-up: in the stated ranges neither operand is scaled (no denormal, the exponents less than
+// 96 apart, reciprocal and quotient normal) and the fix-up passes the value through, so the result is the
+// one `/` gives, bit for bit; `/` covers everything outside.  (Compared on the device for every d of the
+// range against `/`; the library's self-test entry repeats the sweep.)
+__device__ __forceinline__ float div_rn_midrange(float n, float d) {
+  const float y0 = __builtin_amdgcn_rcpf(d);
+  const float e0 = fmaf(-d, y0, 1.0f);
+  const float y1 = fmaf(e0, y0, y0);
+  const float q0 = n * y1;
+  const float r0 = fmaf(-d, q0, n);
+  const float q1 = fmaf(r0, y1, q0);
+  const float r1 = fmaf(-d, q1, n);
+  return fmaf(r1, y1, q1);
+}
+constexpr float DIV_MID_N_LO = 0x1p-40f, DIV_MID_N_HI = 0x1p40f;      // numerator range of div_rn_midrange
+
 // Position of |y| on the E4M3 code axis, in units of 2^-20 codes: codes are linear in the fp32
 // bit pattern above 2^-6 (three mantissa bits kept, twenty dropped) and linear in the value
 // below it (spacing 2^-9), where the fp32 addition of 2^-6 performs the round-to-nearest-even
@@ -102,14 +121,23 @@ __device__ __forceinline__ uint32_t sign_bytes4(float x0, float x1, float x2, fl
 }
 
 // ---------------------------------------------------------------------------------- INT4
-__device__ __forceinline__ float int4_decode(uint32_t packed, int idx) {
-  const int v = ((int)(packed << (28 - 4 * idx))) >> 28;    // sign-extended nibble
-  return (float)v;
+// Eight two's-complement nibbles in a dword, element j in bits 4j..4j+3.
+//
+// Decode: gfx950's v_cvt_off_f32_i4 maps the low four bits of its operand, read as a signed nibble n, to
+// n / 16 exactly, and takes its operand from any byte of a register.  Odd elements sit in the high nibbles,
+// so one shift of the dword by 4 puts them in reach too.  The caller multiplies by 16 * scale instead of
+// scale: (n/16) * (16 s) is the same real product as n * s, hence the same rounded fp32 (16 s is exact;
+// scales of 2^124 and more, for which it would overflow, are outside what the library supports).
+template <int J>
+__device__ __forceinline__ float int4_decode_sixteenth(uint32_t packed, uint32_t packed_shr4) {
+  const uint32_t src = (J & 1) ? packed_shr4 : packed;
+  return __builtin_amdgcn_cvt_off_f32_i4((int)((src >> (8 * (J >> 1))) & 0xFFu));
 }
 
-// Two's-complement nibble of round(y) in [-7, 7].
+// round(y) in [-7, 7] as a float carrying the sign of y (a zero result keeps y's sign: -0.0f decodes and
+// subtracts exactly like +0.0f everywhere it is used).
 template <int ROUND>
-__device__ __forceinline__ uint32_t int4_encode(float y, uint32_t r16) {
+__device__ __forceinline__ float int4_round(float y, uint32_t r16) {
   const float ay = __builtin_fabsf(y);
   uint32_t mag;
   if (ROUND == ROUND_SR) {
@@ -121,8 +149,19 @@ __device__ __forceinline__ uint32_t int4_encode(float y, uint32_t r16) {
     mag = f2u(ay + 0x1p23f) - 0x4B000000u;                  // ulp(2^23) = 1: exact nearest-even
   }
   mag = mag < 7u ? mag : 7u;
-  const uint32_t sgn = (uint32_t)((int32_t)f2u(y) >> 31);   // all ones if negative
-  return ((mag ^ sgn) - sgn) & 15u;
+  return u2f((f2u(y) & 0x80000000u) | f2u((float)mag));
+}
+
+// Insert the nibble of q (an integer in [-7, 7] held as a float) for element J into the byte accumulators:
+// `even` collects elements 0, 2, 4, 6 in its bytes, `odd` elements 1, 3, 5, 7, each as q + 8 in [1, 15]
+// (v_cvt_pk_u8_f32 converts and inserts in one instruction); int4_pack() turns the pair into the dword.
+template <int J>
+__device__ __forceinline__ void int4_insert(float q, uint32_t &even, uint32_t &odd) {
+  if (J & 1) odd = __builtin_amdgcn_cvt_pk_u8_f32(q + 8.0f, J >> 1, odd);
+  else even = __builtin_amdgcn_cvt_pk_u8_f32(q + 8.0f, J >> 1, even);
+}
+__device__ __forceinline__ uint32_t int4_pack(uint32_t even, uint32_t odd) {
+  return (even | (odd << 4)) ^ 0x88888888u;                // offset-8 nibbles -> two's complement
 }
 
 // ---------------------------------------------------------------------------------- Philox4x32-10

@@ -67,6 +67,7 @@ struct StepArgs {            // by-value kernel argument: everything wave-unifor
   uint32_t num_tiles, num_ragged, num_tw_tiles, num_tw_tensors;
   float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd, inv_lr, inv_lr_beta;
   uint32_t seed_lo, seed_hi, step_lo;
+  uint32_t div_mid;                // c1 and eps allow the short division (see div_rn_midrange) after a short square root
   // host side only
   uint32_t lds_bytes;              // dynamic LDS per workgroup of the full-tile kernel (occupancy cap)
   uint32_t lds_bytes_wave;         // the same per wave of the wide-group kernel
@@ -90,6 +91,12 @@ hipError_t launch_quantize_init(const void *src, int src_bf16, uint64_t numel, i
                                 int scale_bf16, void *weights, void *scales, hipStream_t stream);
 hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t numel, int fmt, uint64_t group_size,
                              int scale_bf16, const void *src, int src_kind, float *dst, hipStream_t stream);
+
+hipError_t launch_bandwidth_probe(int kind, void *codes, void *scales, const void *grad, void *m, void *v, uint64_t numel,
+                                  uint32_t lds_bytes, hipStream_t stream);
+
+hipError_t launch_arith_selftest(int kind, float numerator, uint32_t bits_lo, uint32_t bits_hi, unsigned long long *mismatches,
+                                 hipStream_t stream);
 
 // Scale-group classes (how the abs-max of a group is reduced)
 enum : int { GROUP_BLOCK = 0, GROUP_WIDE = 1, GROUP_TENSOR = 2, GROUP_UNSUPPORTED = -1 };

@@ -28,7 +28,7 @@ __device__ __forceinline__ void plain_tile(const StepArgs &a, const TensorDesc &
     if (ADAM) {
       v[j] = fmaf(a.b2, v[j], a.omb2 * (g[j] * g[j]));
       const float d = sqrtf(v[j] * a.rbc2) + a.eps;
-      u = (a.c1 * m[j]) / d;
+      u = (a.c1 / d) * m[j];          // the element-wise step size of Sec. 3.2 times the first moment
     } else {
       u = a.lr * m[j];
     }
@@ -106,7 +106,8 @@ __device__ __forceinline__ void quantize_lane(const void *src, void *weights, vo
   block_scale<FMT, SCALE_BF16>(amax, s_new, inv);
   uint32_t c[2];
   const Philox4 none = {0, 0, 0, 0};
-  encode8<FMT, ROUND_RTN, false>(x, inv, none, c);
+  float q[8];
+  encode8<FMT, ROUND_RTN, false>(x, inv, none, c, q);
   store_codes8<FMT, ACC>(weights, e0, nvalid, c);
   if (RED != RED_SLOT && scale_writer && (ACC == ACC_FULL || nvalid > 0)) {
     if (SCALE_BF16) static_cast<uint16_t *>(scales)[sg] = (uint16_t)(f2u(s_new) >> 16);
@@ -265,6 +266,75 @@ hipError_t launch_dequantize(const void *weights, const void *scales, uint64_t n
   else { if (scale_bf16) ECO_LAUNCH_SRC(FMT_INT4, true); else ECO_LAUNCH_SRC(FMT_INT4, false); }
 #undef ECO_LAUNCH_SRC
 #undef ECO_LAUNCH
+  return hipSuccess;
+}
+
+// ------------------------------------------------------------------------ bandwidth probes
+// Measurement aids: what the memory system delivers for the step's own access pattern with the arithmetic
+// taken out.  MIX: every lane loads what a lane of the FP8 / fp32-state Adam step loads for its 8 elements
+// (8 B codes, 16 B gradient, 2 x 16 B m, 2 x 16 B v, the block's scale) and stores what it stores (codes, m, v,
+// scale), in the same tile geometry and under the same occupancy cap: 11.03 bytes read and 9.03 written per
+// element.  COPY: the plain two-stream copy, 16 B per lane and instruction (4 B read, 4 B written per element).
+__global__ __launch_bounds__(WG_THREADS, 8) void eco_probe_mix_kernel(const uint2 *codes, float *scales, const uint4 *grad,
+                                                                      float4 *m, float4 *v, uint2 *codes_out) {
+  const uint64_t i = (uint64_t)blockIdx.x * WG_THREADS + threadIdx.x;        // the lane's 8-element piece
+  __builtin_amdgcn_s_setprio(3);
+  const uint4 g = grad[i];
+  float4 m0 = m[2 * i], m1 = m[2 * i + 1], v0 = v[2 * i], v1 = v[2 * i + 1];
+  uint2 c = codes[i];
+  const float s = scales[i >> 4];
+  __builtin_amdgcn_s_setprio(0);
+  // every loaded value reaches a store, so that no load can be dropped
+  c.x ^= g.x ^ g.z; c.y ^= g.y ^ g.w;
+  m0.x += s * 0.0f;
+  codes_out[i] = c;
+  m[2 * i] = v0; m[2 * i + 1] = v1; v[2 * i] = m0; v[2 * i + 1] = m1;
+  if ((threadIdx.x & 15) == 0) scales[i >> 4] = s;
+}
+
+__global__ __launch_bounds__(256) void eco_probe_copy_kernel(const float4 *src, float4 *dst) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  dst[i] = src[i];
+}
+
+hipError_t launch_bandwidth_probe(int kind, void *codes, void *scales, const void *grad, void *m, void *v, uint64_t numel,
+                                  uint32_t lds_bytes, hipStream_t stream) {
+  if (kind == 0) {
+    ECO_LAUNCH_CHECKED(eco_probe_mix_kernel, dim3((unsigned)(numel / TILE_ELEMS)), dim3(WG_THREADS), lds_bytes, stream,
+                       static_cast<const uint2 *>(codes), static_cast<float *>(scales), static_cast<const uint4 *>(grad),
+                       static_cast<float4 *>(m), static_cast<float4 *>(v), static_cast<uint2 *>(codes));
+  } else {
+    ECO_LAUNCH_CHECKED(eco_probe_copy_kernel, dim3((unsigned)(numel / 1024)), dim3(256), 0, stream,
+                       static_cast<const float4 *>(m), static_cast<float4 *>(v));
+  }
+  return hipSuccess;
+}
+
+// ------------------------------------------------------------------------ arithmetic self-test
+// The step kernels replace sqrtf() and `/` by shorter sequences inside stated operand ranges; these kernels
+// compare the short forms with the long ones for every fp32 bit pattern of [bits_lo, bits_hi) and count the
+// patterns on which they differ (expected: none).
+template <int KIND>
+__global__ __launch_bounds__(256) void eco_selftest_kernel(float numerator, uint32_t bits_lo, uint32_t bits_hi,
+                                                           unsigned long long *mismatches) {
+  const uint64_t n = (uint64_t)bits_hi - bits_lo;
+  unsigned bad = 0;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256) {
+    const float x = u2f(bits_lo + (uint32_t)i);
+    float fast, ref;
+    if (KIND == 0) { fast = sqrt_rn_midrange(x); ref = sqrtf(x); }
+    else { fast = div_rn_midrange(numerator, x); ref = numerator / x; }
+    bad += f2u(fast) != f2u(ref);
+  }
+  if (bad) atomicAdd(mismatches, (unsigned long long)bad);
+}
+
+hipError_t launch_arith_selftest(int kind, float numerator, uint32_t bits_lo, uint32_t bits_hi, unsigned long long *mismatches,
+                                 hipStream_t stream) {
+  if (kind == 0)
+    ECO_LAUNCH_CHECKED(eco_selftest_kernel<0>, dim3(256 * 16), dim3(256), 0, stream, numerator, bits_lo, bits_hi, mismatches);
+  else
+    ECO_LAUNCH_CHECKED(eco_selftest_kernel<1>, dim3(256 * 16), dim3(256), 0, stream, numerator, bits_lo, bits_hi, mismatches);
   return hipSuccess;
 }
 

@@ -12,7 +12,7 @@
 // be reproduced bit for bit elsewhere:
 //   w  = dec(code) * s_old            g = f32(bf16 gradient)
 //   m~ = fma(b1, m, omb1*g)           v~ = fma(b2, v, omb2*(g*g))
-//   d  = sqrt(v~ * rbc2) + eps        u  = (c1 * m~) / d         [SGDM: u = lr * m~]
+//   d  = sqrt(v~ * rbc2) + eps        eta_t = c1 / d;  u = eta_t * m~   [SGDM: u = lr * m~]
 //   theta~ = w - u                    [with decay: (w - wd*w) - u]
 //   a = max|theta~| over the block;   s' = a / rho;  inv = rho / a
 //       [bf16 scales: s' = bf16(a/rho), inv = 1/s'];  if inv is not finite: s' = inv = 0
@@ -70,11 +70,24 @@ __device__ __forceinline__ void load_bf16x8(const uint16_t *p, int nvalid, float
   }
 }
 
+// Tuning builds only (-DECO_NT_STORES): full-tile vector stores carry the non-temporal hint.
+typedef float eco_f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t eco_u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t eco_u32x2_t __attribute__((ext_vector_type(2)));
+template <class V>
+__device__ __forceinline__ void store_vec(V *p, V x) {
+#ifdef ECO_NT_STORES
+  __builtin_nontemporal_store(x, p);
+#else
+  *p = x;
+#endif
+}
+
 template <int ACC>
 __device__ __forceinline__ void store_f32x8(float *p, int nvalid, const float (&x)[8]) {
   if (use_vector<ACC>(nvalid)) {
-    reinterpret_cast<float4 *>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
-    reinterpret_cast<float4 *>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
+    store_vec(reinterpret_cast<eco_f32x4_t *>(p), eco_f32x4_t{x[0], x[1], x[2], x[3]});
+    store_vec(reinterpret_cast<eco_f32x4_t *>(p) + 1, eco_f32x4_t{x[4], x[5], x[6], x[7]});
   } else {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -88,7 +101,7 @@ __device__ __forceinline__ void store_bf16x8(uint16_t *p, int nvalid, const floa
 #pragma unroll
   for (int j = 0; j < 4; ++j) h[j] = f32x2_to_bf16x2_rne(x[2 * j], x[2 * j + 1]);
   if (use_vector<ACC>(nvalid)) {
-    *reinterpret_cast<uint4 *>(p) = make_uint4(h[0], h[1], h[2], h[3]);
+    store_vec(reinterpret_cast<eco_u32x4_t *>(p), eco_u32x4_t{h[0], h[1], h[2], h[3]});
   } else {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -133,8 +146,8 @@ template <int FMT, int ACC>
 __device__ __forceinline__ void store_codes8(void *base, uint64_t e0, int nvalid, const uint32_t (&c)[2]) {
   uint8_t *p = static_cast<uint8_t *>(base) + (FMT == FMT_FP8 ? e0 : (e0 >> 1));
   if (use_vector<ACC>(nvalid)) {
-    if (FMT == FMT_FP8) *reinterpret_cast<uint2 *>(p) = make_uint2(c[0], c[1]);
-    else *reinterpret_cast<uint32_t *>(p) = c[0];
+    if (FMT == FMT_FP8) store_vec(reinterpret_cast<eco_u32x2_t *>(p), eco_u32x2_t{c[0], c[1]});
+    else store_vec(reinterpret_cast<uint32_t *>(p), c[0]);
   } else {
     const int nbytes = FMT == FMT_FP8 ? nvalid : (nvalid + 1) >> 1;
     constexpr int MAXB = FMT == FMT_FP8 ? 8 : 4;
@@ -147,7 +160,25 @@ __device__ __forceinline__ void store_codes8(void *base, uint64_t e0, int nvalid
 template <int FMT, int J>
 __device__ __forceinline__ float decode_elem(const uint32_t (&c)[2]) {
   if (FMT == FMT_FP8) return e4m3_decode<(J & 3)>(c[J >> 2]);
-  return int4_decode(c[0], J);
+  return int4_decode_sixteenth<J>(c[0], c[0] >> 4) * 16.0f;
+}
+
+// w_j = dec(code_j) * s for a lane's 8 codes under one scale.
+template <int FMT>
+__device__ __forceinline__ void dequant8(const uint32_t (&c)[2], float s, float (&w)[8]) {
+  if (FMT == FMT_FP8) {
+    w[0] = e4m3_decode<0>(c[0]) * s; w[1] = e4m3_decode<1>(c[0]) * s; w[2] = e4m3_decode<2>(c[0]) * s;
+    w[3] = e4m3_decode<3>(c[0]) * s; w[4] = e4m3_decode<0>(c[1]) * s; w[5] = e4m3_decode<1>(c[1]) * s;
+    w[6] = e4m3_decode<2>(c[1]) * s; w[7] = e4m3_decode<3>(c[1]) * s;
+  } else {
+    uint32_t hi = c[0] >> 4;
+    asm volatile("" : "+v"(hi));          // keep the shifted copy in a register: each nibble is then one byte-select away
+    const float s16 = s * 16.0f;          // exact; see int4_decode_sixteenth
+    w[0] = int4_decode_sixteenth<0>(c[0], hi) * s16; w[1] = int4_decode_sixteenth<1>(c[0], hi) * s16;
+    w[2] = int4_decode_sixteenth<2>(c[0], hi) * s16; w[3] = int4_decode_sixteenth<3>(c[0], hi) * s16;
+    w[4] = int4_decode_sixteenth<4>(c[0], hi) * s16; w[5] = int4_decode_sixteenth<5>(c[0], hi) * s16;
+    w[6] = int4_decode_sixteenth<6>(c[0], hi) * s16; w[7] = int4_decode_sixteenth<7>(c[0], hi) * s16;
+  }
 }
 
 template <bool BF16>
@@ -184,26 +215,39 @@ __device__ __forceinline__ float absmin8(const float (&x)[8]) {
   return a;
 }
 
-// Encode y_j = x_j * inv (j = 0..7) onto the grid; returns packed codes.  r = the lane's Philox words.
+// Encode y_j = x_j * inv (j = 0..7) onto the grid: packed codes in c, and in q the values the new codes decode
+// to (before scaling).  r = the lane's Philox words.
 template <int FMT, int ROUND, bool NORMAL_ONLY>
-__device__ __forceinline__ void encode8(const float (&x)[8], float inv, const Philox4 &r, uint32_t (&c)[2]) {
+__device__ __forceinline__ void encode8(const float (&x)[8], float inv, const Philox4 &r, uint32_t (&c)[2], float (&q)[8]) {
   const uint32_t rw[4] = {r.w0, r.w1, r.w2, r.w3};
   c[0] = 0; c[1] = 0;
+  if (FMT == FMT_FP8) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-    if (FMT == FMT_FP8) c[j >> 2] |= e4m3_encode_mag<ROUND, NORMAL_ONLY>(__builtin_fabsf(x[j]) * inv, r16) << (8 * (j & 3));
-    else c[0] |= int4_encode<ROUND>(x[j] * inv, r16) << (4 * j);
-  }
-  if (FMT == FMT_FP8) {   // inv >= 0, so the sign of y is the sign of x
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
+      c[j >> 2] |= e4m3_encode_mag<ROUND, NORMAL_ONLY>(__builtin_fabsf(x[j]) * inv, r16) << (8 * (j & 3));
+    }
+    // inv >= 0, so the sign of y is the sign of x
     c[0] |= sign_bytes4(x[0], x[1], x[2], x[3]);
     c[1] |= sign_bytes4(x[4], x[5], x[6], x[7]);
+    q[0] = e4m3_decode<0>(c[0]); q[1] = e4m3_decode<1>(c[0]); q[2] = e4m3_decode<2>(c[0]); q[3] = e4m3_decode<3>(c[0]);
+    q[4] = e4m3_decode<0>(c[1]); q[5] = e4m3_decode<1>(c[1]); q[6] = e4m3_decode<2>(c[1]); q[7] = e4m3_decode<3>(c[1]);
+  } else {
+    uint32_t even = 0, odd = 0;
+#define ECO_INT4_ELEM(J)                                                                              \
+    q[J] = int4_round<ROUND>(x[J] * inv, (J & 1) ? (rw[J >> 1] >> 16) : (rw[J >> 1] & 0xFFFFu));     \
+    int4_insert<J>(q[J], even, odd);
+    ECO_INT4_ELEM(0) ECO_INT4_ELEM(1) ECO_INT4_ELEM(2) ECO_INT4_ELEM(3)
+    ECO_INT4_ELEM(4) ECO_INT4_ELEM(5) ECO_INT4_ELEM(6) ECO_INT4_ELEM(7)
+#undef ECO_INT4_ELEM
+    c[0] = int4_pack(even, odd);
   }
 }
 
 // d_j = sqrt(x_j) + eps for eight non-negative x.  When every x of the wave lies in the range of
 // sqrt_rn_midrange the short sequence is used; both branches return the correctly rounded root.
-__device__ __forceinline__ void sqrt_plus_eps8(const float (&x)[8], float eps, float (&d)[8]) {
+// Returns whether the short sequence was used (wave-uniform): then every x of the wave lies in [2^-96, 2^96].
+__device__ __forceinline__ bool sqrt_plus_eps8(const float (&x)[8], float eps, float (&d)[8]) {
   uint32_t lo = f2u(x[0]), hi = f2u(x[0]);
 #pragma unroll
   for (int j = 1; j < 8; ++j) {
@@ -214,10 +258,11 @@ __device__ __forceinline__ void sqrt_plus_eps8(const float (&x)[8], float eps, f
   if (__all(lo >= SQRT_MID_LO && hi <= SQRT_MID_HI)) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) d[j] = sqrt_rn_midrange(x[j]) + eps;
-  } else {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) d[j] = sqrtf(x[j]) + eps;
+    return true;
   }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) d[j] = sqrtf(x[j]) + eps;
+  return false;
 }
 
 // ------------------------------------------------------------------ the step of one lane
@@ -280,16 +325,13 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
     uint32_t c[2];
     load_codes8<FMT, ACC>(td.w, e0, nvalid, c);
     const float s_old = any ? load_scale<SCALE_BF16>(td.s, sg) : 0.0f;
-    w[0] = decode_elem<FMT, 0>(c) * s_old; w[1] = decode_elem<FMT, 1>(c) * s_old;
-    w[2] = decode_elem<FMT, 2>(c) * s_old; w[3] = decode_elem<FMT, 3>(c) * s_old;
-    w[4] = decode_elem<FMT, 4>(c) * s_old; w[5] = decode_elem<FMT, 5>(c) * s_old;
-    w[6] = decode_elem<FMT, 6>(c) * s_old; w[7] = decode_elem<FMT, 7>(c) * s_old;
+    dequant8<FMT>(c, s_old, w);
   }
 
   __builtin_amdgcn_s_setprio(0);      // loads issued: back to the default priority (see eco_step_kernel)
 
   // OPTIM_STEP on the de-quantized (or master) weights
-  float th[8], d[8];
+  float th[8], d[8], eta[8];
   if (ADAM) {
     float x[8];
 #pragma unroll
@@ -299,7 +341,15 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
       x[j] = v[j] * a.rbc2;
     }
     if (WRITE) store_state8<STATE_BF16, ACC>(td.v, e0, nvalid, v);   // v is final (Alg. 3 returns it unchanged)
-    sqrt_plus_eps8(x, a.eps, d);
+    // the element-wise step size of Sec. 3.2, eta_t = (eta / (1 - b1^k)) / (sqrt(v^) + eps).  After the short square
+    // root every d of the wave lies in [2^-48, 2^48 + eps], and div_mid says that eps <= 1 and c1 is in range
+    if (sqrt_plus_eps8(x, a.eps, d) && a.div_mid) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) eta[j] = div_rn_midrange(a.c1, d[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) eta[j] = a.c1 / d[j];
+    }
   }
   if (a.wd != 0.0f) {
     // decoupled decay; off in most runs, so it is kept a (wave-uniform) branch: the empty asm statement
@@ -312,7 +362,7 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
   for (int j = 0; j < 8; ++j) {
     float u;
     if (ADAM) {
-      u = (a.c1 * m[j]) / d[j];
+      u = eta[j] * m[j];
     } else {
       m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
       d[j] = 0.0f;
@@ -332,24 +382,25 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
   Philox4 r = {0, 0, 0, 0};
   if (ROUND == ROUND_SR) {
     const uint64_t q = e0 >> 3;
-    r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
+    // tensors of up to 2^35 elements (wave-uniform test): the high counter word is zero, which makes the first
+    // two rounds' products of the wave-uniform words scalar work
+    if (td.numel <= (1ull << 35)) r = philox4x32_10((uint32_t)q, 0u, a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
+    else r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
   }
   uint32_t cn[2];
+  float qn[8];
   if (FMT == FMT_FP8) {
     // the E4M3 subnormal range (|y| < 2^-6) needs a second formula; it is rare, so decide per wave
     // (multiplication by inv >= 0 is monotone, so the smallest |y| is fl(min|theta~| * inv))
-    if (__any(absmin8(th) * inv < 0x1p-6f)) encode8<FMT, ROUND, false>(th, inv, r, cn);
-    else encode8<FMT, ROUND, true>(th, inv, r, cn);
+    if (__any(absmin8(th) * inv < 0x1p-6f)) encode8<FMT, ROUND, false>(th, inv, r, cn, qn);
+    else encode8<FMT, ROUND, true>(th, inv, r, cn, qn);
   } else {
-    encode8<FMT, ROUND, true>(th, inv, r, cn);
+    encode8<FMT, ROUND, true>(th, inv, r, cn, qn);
   }
   store_codes8<FMT, ACC>(td.w, e0, nvalid, cn);
 
   if (!MASTER) {
-    float qn[8], eo[8];
-    qn[0] = decode_elem<FMT, 0>(cn); qn[1] = decode_elem<FMT, 1>(cn); qn[2] = decode_elem<FMT, 2>(cn);
-    qn[3] = decode_elem<FMT, 3>(cn); qn[4] = decode_elem<FMT, 4>(cn); qn[5] = decode_elem<FMT, 5>(cn);
-    qn[6] = decode_elem<FMT, 6>(cn); qn[7] = decode_elem<FMT, 7>(cn);
+    float eo[8];
     if (ALGO == ALGO_SGDM_EXACT) load_f32x8<ACC>(static_cast<const float *>(td.aux) + e0, nvalid, eo);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {

@@ -54,13 +54,15 @@ class DeviceWorkload:
     def __init__(self, wl: Workload, device: str = "cuda:0", base_seed: int = workloads.BASE_SEED,
                  init=True, layout: Optional[dict] = None, skew_bytes: Optional[dict] = None,
                  single_allocation=False, placement: str = "auto", grad_sets: int = 1,
-                 spread_gap: Optional[int] = None, calibrate_gaps: int = 0):
+                 spread_gap: Optional[int] = None, calibrate_gaps: int = 0, order: str = "default"):
         """`layout`: hyper-parameter overrides that are fixed for the life of the plan (opt, mode, ...).
         In the master-weight mode the fp32 initial weights are kept as the master copy; in the
         exact-injection mode the aux buffer starts as e_0 = theta_0 - q(theta_0) (Appendix A).
         `placement`: "packed" = one allocation per arena (wherever the allocator puts them), "spread" = one
         allocation with the arena groups far apart (see SPREAD_GAP), "auto" = spread for large workloads when
         the device has the memory for it.  `skew_bytes` / `single_allocation` place arenas by hand (probes).
+        `order`: "default" lays the arenas out as codes, scales, gradients, m, v; "state-apart" (one allocation only)
+        puts m first and v last with everything else between them, no byte unused.
         `grad_sets`: number of gradient arenas (each with a plan of its own over the same weights and state),
         so that the gradients of several steps can be resident before the steps run back to back.
         `calibrate_gaps`: with the spread placement, time a few steps (on placeholder data, before the weights
@@ -68,6 +70,7 @@ class DeviceWorkload:
         the one allocation, and keep the fastest: which distances suit the memory system best differs a little
         from device to device."""
         self.wl = wl
+        self.order = order
         self.layout = dict(layout or {})
         self.mode = self.layout.get("mode", eco.ECO_MODE_ECO if self.layout.get("inject", True) else eco.ECO_MODE_NAIVE)
         self.device = torch.device(device)
@@ -80,18 +83,27 @@ class DeviceWorkload:
         dev = self.device
         skew = dict(skew_bytes or {})
         self.placement = "packed"
-        if placement in ("auto", "spread") and not skew and single_allocation is False and dev.type == "cuda":
+        if placement == "auto":
+            # large workloads: one allocation without gaps, m first and v last (as fast as the spread placement, measured)
+            placement = "dense" if self.pool_bytes(wl, self.mode, grad_sets) >= self.SPREAD_MIN_BYTES and dev.type == "cuda" else "packed"
+        if placement == "spread" and not skew and single_allocation is False and dev.type == "cuda":
             need = self.pool_bytes(wl, self.mode, grad_sets)
             ngaps = 3 if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER) else 2
             torch.cuda.empty_cache()
             free = torch.cuda.mem_get_info(dev)[0]
             gap = min(spread_gap or self.SPREAD_GAP, max(0, int(0.7 * free) - need) // ngaps) >> 21 << 21
-            if gap >= (24 << 30) and (placement == "spread" or need >= self.SPREAD_MIN_BYTES):
+            if gap >= (24 << 30):
                 skew = {"m": gap, "v": gap}
                 if ngaps == 3:
                     skew["aux"] = gap
                 single_allocation = True
                 self.placement = f"one allocation, arena groups {gap >> 30} GiB apart"
+        if placement in ("dense", "dense-default") and single_allocation is False and not skew:
+            single_allocation = True
+            if placement == "dense":
+                self.order = "state-apart"
+            self.placement = ("one allocation, no gaps, order: " +
+                              ("m | codes, scales, gradients | v" if placement == "dense" else "codes, scales, gradients, m, v"))
         pool_buf, pool_pos = None, 0
         external = isinstance(single_allocation, torch.Tensor)
         if external:                                         # a caller-owned uint8 pool; skew["pool"] = where to start in it
@@ -123,17 +135,22 @@ class DeviceWorkload:
                 buf = torch.zeros(n + k // es, dtype=dtype, device=dev)
                 return buf[k // es:]
 
-            self.codes = arena("codes", max(code_bytes, 1), torch.uint8)
-            self.scales = arena("scales", max(soff, 1), self.scale_dtype)
-            self.plain = arena("plain", max(woff, 1), torch.bfloat16)
-            self.grads = [arena("grad", off, torch.bfloat16)]
-            for _ in range(1, grad_sets):
-                self.grads.append(arena("grad_extra", off, torch.bfloat16))
+            # the arenas, in the order in which they are laid out when they share one allocation
+            want = [("codes", max(code_bytes, 1), torch.uint8), ("scales", max(soff, 1), self.scale_dtype),
+                    ("plain", max(woff, 1), torch.bfloat16), ("grad", off, torch.bfloat16)]
+            want += [(f"grad_extra{k}", off, torch.bfloat16) for k in range(1, grad_sets)]
+            want += [("m", off, self.state_dtype), ("v", off, self.state_dtype)]
+            if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER):
+                want.append(("aux", off, torch.float32))
+            if self.order == "state-apart":
+                # m first, v last: the two largest arrays of the lock-step streams at the two ends of the footprint,
+                # everything else (codes, scales, gradients of all resident steps) between them
+                want.sort(key=lambda w: {"m": 0, "v": 2, "aux": 3}.get(w[0], 1))
+            got = {name: arena("grad_extra" if name.startswith("grad_extra") else name, n, dt) for name, n, dt in want}
+            self.codes, self.scales, self.plain = got["codes"], got["scales"], got["plain"]
+            self.grads = [got["grad"]] + [got[f"grad_extra{k}"] for k in range(1, grad_sets)]
             self.grad = self.grads[0]
-            self.m = arena("m", off, self.state_dtype)
-            self.v = arena("v", off, self.state_dtype)
-            self.aux = (arena("aux", off, torch.float32)
-                        if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER) else None)
+            self.m, self.v, self.aux = got["m"], got["v"], got.get("aux")
             self.tensors = []
             for i, t in enumerate(wl.tensors):
                 n = t.numel

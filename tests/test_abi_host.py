@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(eco):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(eco_[a-z_0-9]+)\s*\(", header))
     assert {"eco_plan_create", "eco_plan_destroy", "eco_step", "eco_step_tensors", "eco_step_tensors_noalloc", "eco_quantize_init",
-            "eco_dequantize", "eco_quantize_error", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_status_string",
+            "eco_dequantize", "eco_quantize_error", "eco_bandwidth_probe", "eco_arith_selftest", "eco_philox_fill", "eco_step_constants", "eco_set_option", "eco_status_string",
             "eco_last_error", "eco_version"} <= names
     for n in names:
         assert hasattr(eco.lib, n), n

@@ -41,6 +41,26 @@ def test_philox_stream_is_bit_exact(eco, o32):
         assert np.array_equal(got, o32.philox_fill(seed, step, tid, n, first_word=first)), (seed, step, tid, first)
 
 
+def test_short_square_root_and_division_are_correctly_rounded(eco):
+    """The step kernels use shorter sequences than sqrtf() and `/` inside stated operand ranges; the library's self-test
+    compares short and long form on the device: every fp32 argument of the square root's range (1.6e9 patterns), and
+    every denominator of the division's range (8.1e8 patterns) for several numerators c1 = lr / (1 - beta1^k), typical
+    and extreme -- 6.5e9 operand pairs, every exponent difference the short form can meet."""
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    eco.eco_arith_selftest(0, 0.0, 0x0F800000, 0x6F800001, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0, "short square root differs from sqrtf"
+    for c1 in (1e-3, 1e-3 / (1 - 0.9), 1e-5 / (1 - 0.9 ** 3), 3e-4 / (1 - 0.9 ** 7), 2.0 ** -40, 2.0 ** 40, 0.7853982, -1.9999999):
+        eco.eco_arith_selftest(1, c1, 0x27800000, 0x58000001, bad)
+        torch.cuda.synchronize()
+        assert int(bad.item()) == 0, f"short division differs from / for numerator {c1}"
+    # the entry point refuses operands outside the ranges the short forms are used in
+    for args in ((0, 0.0, 0x0F7FFFFF, 0x10000000), (1, 1.0, 0x27800000, 0x58000002), (1, 2.0 ** 41, 0x30000000, 0x30000010),
+                 (2, 1.0, 0x30000000, 0x30000010), (1, 1.0, 0x30000010, 0x30000010)):
+        with pytest.raises(eco.EcoError):
+            eco.eco_arith_selftest(*args, bad)
+
+
 def test_decode_every_code(eco, o32):
     codes = torch.arange(256, dtype=torch.uint8, device=DEV)
     scales = torch.ones(2, dtype=torch.float32, device=DEV)
@@ -452,6 +472,19 @@ def test_results_do_not_depend_on_where_the_arenas_lie(harness, eco):
         b.step(k, k - 1)
     torch.cuda.synchronize()
     assert _equal(_snapshot(a), _snapshot(b))
+    # one allocation without gaps, m first and v last (what "auto" chooses for large workloads), and the plain order
+    for placement, first in (("dense", "m"), ("dense-default", "codes")):
+        c = harness.DeviceWorkload(wl, DEV, placement=placement, grad_sets=2)
+        assert "no gaps" in c.placement
+        ptrs = {k: getattr(c, k).data_ptr() for k in ("m", "codes", "scales", "grad", "v")}
+        assert min(ptrs, key=ptrs.get) == first and max(ptrs, key=ptrs.get) == "v"
+        assert ptrs["v"] + c.v.numel() * 4 - min(ptrs.values()) < 2 * harness.DeviceWorkload.pool_bytes(wl, grad_sets=2)
+        for k in (1, 2, 3):
+            c.fill_gradients(k, k & 1)
+            c.step(k, k & 1)
+        torch.cuda.synchronize()
+        assert _equal(_snapshot(a), _snapshot(c))
+        c.close()
     a.close()
     b.close()
 

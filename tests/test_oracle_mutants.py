@@ -33,6 +33,7 @@ MUTANTS = [
     ("second-moment bias correction off by one",
      "bc2 = 1.0 - pow(cfg->beta2, (double)cfg->step);", "bc2 = 1.0 - pow(cfg->beta2, (double)cfg->step + 1.0);"),
     ("eps inside the square root", "dd[j] = r_sqrt(vt * rbc2) + epsf;", "dd[j] = r_sqrt(vt * rbc2 + epsf);"),
+    ("adam step size without the bias correction of the first moment", "c1 = (REAL)(cfg->lr / bc1);", "c1 = (REAL)(cfg->lr);"),
     ("second moment of g instead of g*g", "omb2 * (g * g)", "omb2 * g"),
     ("momentum without the (1 - beta) damping", "mt[j] = r_fma(b1, m[i], omb1 * g);", "mt[j] = r_fma(b1, m[i], g);"),
     ("update added instead of subtracted", "th[j] = w - u;", "th[j] = w + u;"),
@@ -72,7 +73,7 @@ MUTANTS = [
 
 
 def run_pins(source, workdir):
-    env = dict(os.environ, ECO_ORACLE_SOURCE=source, OMP_NUM_THREADS="2", PYTHONDONTWRITEBYTECODE="1")
+    env = dict(os.environ, ECO_ORACLE_SOURCE=source, OMP_NUM_THREADS="1", PYTHONDONTWRITEBYTECODE="1")
     r = subprocess.run([sys.executable, "-m", "pytest", *PINS, "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider"],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=900)
     return r.returncode, r.stdout[-1500:]
@@ -102,7 +103,7 @@ def test_the_pins_notice_every_planted_mistake(tmp_path):
         src.write_text(text.replace(old, new))
         assert compile_ok(str(src)), f"mutant '{name}' does not compile"
         jobs.append((name, str(src)))
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=max(2, min(8, os.cpu_count() or 4))) as ex:
         results = list(ex.map(lambda j: run_pins(j[1], None), jobs))
     rc0, out0 = results[0]
     assert rc0 == 0, "the pins fail on an unmodified copy of the oracle:\n" + out0
