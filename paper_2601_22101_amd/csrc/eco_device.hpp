@@ -135,16 +135,20 @@ __device__ __forceinline__ float int4_decode_sixteenth(uint32_t packed, uint32_t
 }
 
 // round(y) in [-7, 7] as a float carrying the sign of y (a zero result keeps y's sign: -0.0f decodes and
-// subtracts exactly like +0.0f everywhere it is used).
+// subtracts exactly like +0.0f everywhere it is used).  Needs |y| < 8 + 2^-3, which abs-max scaling guarantees
+// (|y| <= 7 (1 + 2^-8) even when a bf16 scale was rounded down).
 template <int ROUND>
 __device__ __forceinline__ float int4_round(float y, uint32_t r16) {
   const float ay = __builtin_fabsf(y);
   uint32_t mag;
   if (ROUND == ROUND_SR) {
-    // ulp(8.0) = 2^-20: the addition rounds |y| to nearest-even multiples of 2^-20
-    // (for |y| >= 8 the bit pattern keeps growing, so the result saturates below)
-    const uint32_t k = f2u(ay + 8.0f) - (0x41000000u - SR_CENTRE);
-    mag = (k + (r16 << 4)) >> 20;                           // up iff frac20 + 16*r16 + 8 >= 2^20
+    // ulp(8.0) = 2^-20: the addition rounds |y| to the nearest-even multiple of 2^-20 and puts it, as a 4.20
+    // fixed-point number, into the low 24 bits of the result.  The addend also carries the centring term of the
+    // rounding rule, 8 units of 2^-20 -- an exact multiple of the ulp, so it commutes with the rounding -- which
+    // leaves "up iff frac20 + 16*r16 + 8 >= 2^20" as one shift-and-add and a bit-field extract.  (|y| + 8 + 2^-17
+    // can reach the next binade only for |y| > 7.9999, where bit 23 is set and the result saturates at 7 anyway.)
+    const uint32_t t = f2u(ay + (8.0f + 0x1p-17f)) + (r16 << 4);
+    mag = (t >> 20) & 15u;
   } else {
     mag = f2u(ay + 0x1p23f) - 0x4B000000u;                  // ulp(2^23) = 1: exact nearest-even
   }

@@ -382,10 +382,15 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
   Philox4 r = {0, 0, 0, 0};
   if (ROUND == ROUND_SR) {
     const uint64_t q = e0 >> 3;
-    // tensors of up to 2^35 elements (wave-uniform test): the high counter word is zero, which makes the first
-    // two rounds' products of the wave-uniform words scalar work
-    if (td.numel <= (1ull << 35)) r = philox4x32_10((uint32_t)q, 0u, a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
-    else r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
+    // tensors of up to 2^35 elements (a wave-uniform, scalar test): the high counter word is zero, so the words
+    // that enter the first two rounds beside q are all wave-uniform and their products are scalar work (the
+    // empty asm statement keeps the two calls apart: merged, the zero would become a per-lane select)
+    if (td.numel <= (1ull << 35)) {
+      r = philox4x32_10((uint32_t)q, 0u, a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
+      asm volatile("" ::: "memory");
+    } else {
+      r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.step_lo, td.tensor_id, a.seed_lo, a.seed_hi);
+    }
   }
   uint32_t cn[2];
   float qn[8];
