@@ -274,7 +274,7 @@ eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out);
  *   option 2: the same per wave of the wide-group and tensor-wise kernels (-1 = library default) */
 eco_status_t eco_set_option(int32_t option, int64_t value);
 
-const char *eco_status_string(eco_status_t status);
+const char *eco_status_string(int status);   /* status: an eco_status_t; any other value gives "unknown status" */
 const char *eco_last_error(void);   /* thread-local, never NULL */
 int eco_version(void);              /* major*10000 + minor*100 + patch */
 

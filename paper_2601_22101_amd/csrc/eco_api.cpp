@@ -338,7 +338,7 @@ struct eco_plan {
 
 extern "C" {
 
-const char *eco_status_string(eco_status_t s) {
+const char *eco_status_string(int s) {
   switch (s) {
     case ECO_OK: return "ok";
     case ECO_EINVAL: return "invalid argument";
