@@ -47,10 +47,10 @@
  *    called from any thread.
  *
  * Performance notes for callers (MI355X; none of this changes results)
- *  - The step is bound by HBM bandwidth.  The arrays of a tensor are streamed in lock-step; on MI355X they
- *    run several per cent faster when the gradient/code, m and v arrays lie tens of GiB apart in device
- *    memory (for example in different parts of one large allocation) than when they are packed next to each
- *    other.
+ *  - The step is bound by HBM bandwidth (the INT4 / bf16-state form by vector-ALU issue) and runs at the rate
+ *    of a plain copy kernel on the same arrays.  The arrays of a tensor are streamed in lock-step; where they
+ *    lie in device memory relative to each other (packed, or tens of GiB apart) moves the step time by about
+ *    one per cent, less than the difference between two processes.
  *  - One plan over all tensors of a model is one kernel launch per storage format; per-tensor calls pay a
  *    launch each.
  *  - Tensor lengths that are multiples of 512 keep every tile on the unguarded fast path.
