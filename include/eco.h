@@ -207,6 +207,10 @@ eco_status_t eco_step_tensors_noalloc(const eco_tensor_t *tensors, size_t n, con
  * With one scale for a tensor of more than 8192 elements the abs-max is kept in a library-owned slot between
  * the call's kernels; the library hands out 64 such slots in turn and makes a call wait, on its own stream, for
  * the previous user of its slot, so calls on different streams may overlap.
+ * Size limit, for this call, eco_dequantize and eco_quantize_error alike: what one kernel launch holds (fewer than
+ * 2^32 threads, one thread per 8 elements: just under 2^35 elements; less for groups of 520..8192 elements whose
+ * length is far from a multiple of 512).  Larger arrays are ECO_EUNSUPPORTED: pass slices of whole scale groups.
+ * (eco_step and eco_step_tensors have no such limit: they launch in pieces.)
  */
 eco_status_t eco_quantize_init(const void *src, int32_t src_dtype, uint64_t numel, int32_t fmt, uint64_t group_size,
                                int32_t scale_dtype, void *weights, void *scales, void *stream);
@@ -271,7 +275,10 @@ eco_status_t eco_step_constants(const eco_hparams_t *hp, eco_constants_t *out);
  *             tiles (0 = library default: one workgroup per 512-element tile, no cap)
  *   option 1: bytes of dynamic LDS requested per workgroup of the step kernel (-1 = library default).
  *             The kernel never touches it; the request only caps resident workgroups per compute unit.
- *   option 2: the same per wave of the wide-group and tensor-wise kernels (-1 = library default) */
+ *   option 2: the same per wave of the wide-group and tensor-wise kernels (-1 = library default)
+ *   option 3: most threads one kernel launch of a step may have, in [1024, 2^32 - 1] (-1 = the runtime's limit,
+ *             2^32 - 1).  A step with more work items than that launches its kernels in several pieces; a small
+ *             value lets a test take that path with a small plan. */
 eco_status_t eco_set_option(int32_t option, int64_t value);
 
 const char *eco_status_string(int status);   /* status: an eco_status_t; any other value gives "unknown status" */

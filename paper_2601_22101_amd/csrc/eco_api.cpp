@@ -21,6 +21,7 @@ namespace {
 thread_local std::string g_last_error;
 // launch tuning (eco_set_option): read by every eco_step, possibly from other host threads
 std::atomic<int64_t> g_wgs_per_cu{0};        // 0 = default
+std::atomic<int64_t> g_max_launch_threads{-1};   // -1 = the runtime's limit; smaller values make the step launch in chunks
 std::atomic<int64_t> g_lds_bytes{-1};        // -1 = default; dynamic LDS per workgroup of the step kernel (occupancy limiter)
 std::atomic<int64_t> g_lds_bytes_wave{-1};   // -1 = default; the same per wave of the wide-group and tensor-wise kernels
 
@@ -138,7 +139,7 @@ int default_waves(const eco::KernelVariant &kv) {
     case eco::ALGO_ADAM: return 12;          // 20.1 B/parameter
     case eco::ALGO_ADAM_MASTER: return 8;    // 27.0
     case eco::ALGO_SGDM: return 14;          // 12.1
-    case eco::ALGO_SGDM_MASTER: return 10;   // 19.0
+    case eco::ALGO_SGDM_MASTER: return 8;    // 19.0
     default: return 11;                      // SGDM with a stored error: 20.1
   }
 }
@@ -218,6 +219,9 @@ void fill_step_scalars(const eco_hparams_t *hp, const eco_constants_t &c, const 
   a->seed_hi = static_cast<uint32_t>(hp->seed >> 32);
   a->step_lo = static_cast<uint32_t>(hp->step);
   a->div_mid = (c.c1 >= 0x1p-40f && c.c1 <= 0x1p40f && c.eps <= 1.0f) ? 1u : 0u;
+  const int64_t opt_threads = g_max_launch_threads.load(std::memory_order_relaxed);
+  a->max_launch_threads = opt_threads > 0 ? static_cast<uint64_t>(opt_threads) : eco::MAX_LAUNCH_THREADS;
+  a->unit_base = 0;
   const int waves = default_waves(kv);
   const int waves_wide = kv.algo == eco::ALGO_ADAM ? waves : 0;     // measured for Adam only; SGDM ran best uncapped
   const int64_t opt_lds = g_lds_bytes.load(std::memory_order_relaxed);
@@ -368,6 +372,12 @@ eco_status_t eco_set_option(int32_t option, int64_t value) {
   if (option == 2) {
     if (value < -1 || value > 32768) return fail(ECO_EINVAL, "LDS bytes per wave must lie in [-1, 32768]");
     g_lds_bytes_wave = value;
+    return ECO_OK;
+  }
+  if (option == 3) {
+    if (value != -1 && (value < 1024 || value > static_cast<int64_t>(eco::MAX_LAUNCH_THREADS)))
+      return fail(ECO_EINVAL, "threads per launch must be -1 or lie in [1024, 2^32 - 1]");
+    g_max_launch_threads = value;
     return ECO_OK;
   }
   return fail(ECO_EINVAL, "unknown option %d", option);
@@ -689,6 +699,9 @@ static eco_status_t check_flat(const void *weights, const void *scales, uint64_t
   if (group_size == 0) return fail(ECO_EINVAL, "group_size must be positive");
   if (!weights || !scales) return fail(ECO_EINVAL, "null weights or scales");
   if (!aligned16(weights) || !aligned16(scales)) return fail(ECO_EALIGN, "weights and scales must be 16-byte aligned");
+  if (!eco::flat_call_fits(numel, group_size))
+    return fail(ECO_EUNSUPPORTED, "%llu elements in groups of %llu: one call handles what one launch can (about 2^35 elements); "
+                "call it on slices of whole scale groups", (unsigned long long)numel, (unsigned long long)group_size);
   return ECO_OK;
 }
 
@@ -743,8 +756,8 @@ eco_status_t eco_bandwidth_probe(int32_t kind, void *codes, void *scales, const 
   if (!m || !v || (kind == 0 && (!codes || !scales || !grad))) return fail(ECO_EINVAL, "null array");
   if (!aligned16(m) || !aligned16(v) || (kind == 0 && (!aligned16(codes) || !aligned16(scales) || !aligned16(grad))))
     return fail(ECO_EALIGN, "every array must be 16-byte aligned");
-  if (numel == 0 || numel % 1024 != 0 || numel / eco::TILE_ELEMS > 0x7FFFFFFFull)
-    return fail(ECO_EINVAL, "numel must be a positive multiple of 1024 below 2^40");
+  if (numel == 0 || numel % 1024 != 0 || numel / eco::ELEMS_PER_LANE > eco::MAX_LAUNCH_THREADS)
+    return fail(ECO_EINVAL, "numel must be a positive multiple of 1024 below 2^35");
   eco::KernelVariant kv;
   kv.fmt = eco::FMT_FP8; kv.state_bf16 = 0; kv.scale_bf16 = 0; kv.algo = eco::ALGO_ADAM; kv.round = eco::ROUND_SR;
   const int64_t opt_lds = g_lds_bytes.load(std::memory_order_relaxed);

@@ -68,7 +68,9 @@ struct StepArgs {            // by-value kernel argument: everything wave-unifor
   float b1, omb1, b2, omb2, rbc2, c1, eps, kappa, lr, alpha, wd, inv_lr, inv_lr_beta;
   uint32_t seed_lo, seed_hi, step_lo;
   uint32_t div_mid;                // c1 and eps allow the short division (see div_rn_midrange) after a short square root
+  uint32_t unit_base;              // first work item (group, tile, tensor) of the launch in flight, see launch_in_chunks
   // host side only
+  uint64_t max_launch_threads;     // most threads one launch may have (the runtime's limit, or a smaller one set for tests)
   uint32_t lds_bytes;              // dynamic LDS per workgroup of the full-tile kernel (occupancy cap)
   uint32_t lds_bytes_wave;         // the same per wave of the wide-group kernel
   uint32_t lds_bytes_tw;           // the same per (one-wave) workgroup of the two tensor-wise passes
@@ -106,6 +108,18 @@ inline int classify_group(uint64_t group_size, uint64_t numel) {
   if (g <= MAX_WIDE_GROUP && g % 8 == 0) return GROUP_WIDE;
   if (group_size >= numel) return GROUP_TENSOR;
   return GROUP_UNSUPPORTED;
+}
+// The helper kernels (initial quantizer, de-quantizer, error) take one launch with one workgroup per tile or per
+// wide group, and the runtime wants grid x block below 2^32: about 2^35 elements a call.
+constexpr uint64_t MAX_LAUNCH_THREADS = 0xFFFFFFFFull;
+inline bool flat_call_fits(uint64_t numel, uint64_t group_size) {
+  if (numel > (1ull << 40)) return false;
+  uint64_t threads = (numel + TILE_ELEMS - 1) / TILE_ELEMS * WG_THREADS;
+  if (classify_group(group_size, numel) == GROUP_WIDE) {
+    const uint64_t g = group_size < numel ? group_size : numel;
+    threads = (numel + g - 1) / g * 64 * ((g + TILE_ELEMS - 1) / TILE_ELEMS);
+  }
+  return threads <= MAX_LAUNCH_THREADS;
 }
 inline int log2_exact(uint64_t x) {
   for (int s = 0; s < 64; ++s)

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(WG_THREADS) void eco_plain_kernel(const StepArgs a)
 
 template <int FMT, bool STATE_BF16, bool ADAM>
 __global__ __launch_bounds__(WG_THREADS) void eco_plain_ragged_kernel(const StepArgs a) {
-  const TensorDesc td = load_tensor_desc(a, load_table(a.ragged_tensor, blockIdx.x));
+  const TensorDesc td = load_tensor_desc(a, load_table(a.ragged_tensor, blockIdx.x + a.unit_base));
   const uint64_t tile_off = td.numel / TILE_ELEMS * TILE_ELEMS;
   plain_tile<FMT, STATE_BF16, ADAM, ACC_GUARDED>(a, td, tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE);
 }
@@ -60,10 +60,10 @@ hipError_t launch_step_plain(const KernelVariant &kv, const StepArgs &args, unsi
 #define ECO_LAUNCH(F, ST, AD)                                                                                  \
   do {                                                                                                         \
     if (args.num_tiles)                                                                                        \
-      ECO_LAUNCH_CHECKED((eco_plain_kernel<F, ST, AD>), dim3(grid), dim3(WG_THREADS), 0, stream, args);        \
-    if (args.num_ragged)                                                                                       \
-      ECO_LAUNCH_CHECKED((eco_plain_ragged_kernel<F, ST, AD>), dim3(args.num_ragged), dim3(WG_THREADS), 0,     \
+      ECO_LAUNCH_CHECKED((eco_plain_kernel<F, ST, AD>), dim3(capped_grid(grid, args)), dim3(WG_THREADS), 0,    \
                          stream, args);                                                                        \
+    if (args.num_ragged)                                                                                       \
+      ECO_CHUNKS_CHECKED((eco_plain_ragged_kernel<F, ST, AD>), args.num_ragged, WG_THREADS, 0, stream, args);  \
   } while (0)
   const int key = (kv.fmt == FMT_FP32_ID ? 4 : 0) | (kv.state_bf16 ? 2 : 0) | (algo_is_adam(kv.algo) ? 0 : 1);
   switch (key) {

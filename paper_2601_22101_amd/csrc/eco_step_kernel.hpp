@@ -163,22 +163,22 @@ __device__ __forceinline__ float decode_elem(const uint32_t (&c)[2]) {
   return int4_decode_sixteenth<J>(c[0], c[0] >> 4) * 16.0f;
 }
 
-// w_j = dec(code_j) * s for a lane's 8 codes under one scale.
+// The decoded values dq_j of a lane's 8 codes and the factor sc with w_j = dq_j * sc (INT4 decodes to
+// sixteenths, so sc = 16 s there: exact, see int4_decode_sixteenth).
 template <int FMT>
-__device__ __forceinline__ void dequant8(const uint32_t (&c)[2], float s, float (&w)[8]) {
+__device__ __forceinline__ float decode8(const uint32_t (&c)[2], float s, float (&dq)[8]) {
   if (FMT == FMT_FP8) {
-    w[0] = e4m3_decode<0>(c[0]) * s; w[1] = e4m3_decode<1>(c[0]) * s; w[2] = e4m3_decode<2>(c[0]) * s;
-    w[3] = e4m3_decode<3>(c[0]) * s; w[4] = e4m3_decode<0>(c[1]) * s; w[5] = e4m3_decode<1>(c[1]) * s;
-    w[6] = e4m3_decode<2>(c[1]) * s; w[7] = e4m3_decode<3>(c[1]) * s;
-  } else {
-    uint32_t hi = c[0] >> 4;
-    asm volatile("" : "+v"(hi));          // keep the shifted copy in a register: each nibble is then one byte-select away
-    const float s16 = s * 16.0f;          // exact; see int4_decode_sixteenth
-    w[0] = int4_decode_sixteenth<0>(c[0], hi) * s16; w[1] = int4_decode_sixteenth<1>(c[0], hi) * s16;
-    w[2] = int4_decode_sixteenth<2>(c[0], hi) * s16; w[3] = int4_decode_sixteenth<3>(c[0], hi) * s16;
-    w[4] = int4_decode_sixteenth<4>(c[0], hi) * s16; w[5] = int4_decode_sixteenth<5>(c[0], hi) * s16;
-    w[6] = int4_decode_sixteenth<6>(c[0], hi) * s16; w[7] = int4_decode_sixteenth<7>(c[0], hi) * s16;
+    dq[0] = e4m3_decode<0>(c[0]); dq[1] = e4m3_decode<1>(c[0]); dq[2] = e4m3_decode<2>(c[0]); dq[3] = e4m3_decode<3>(c[0]);
+    dq[4] = e4m3_decode<0>(c[1]); dq[5] = e4m3_decode<1>(c[1]); dq[6] = e4m3_decode<2>(c[1]); dq[7] = e4m3_decode<3>(c[1]);
+    return s;
   }
+  uint32_t hi = c[0] >> 4;
+  asm volatile("" : "+v"(hi));          // keep the shifted copy in a register: each nibble is then one byte-select away
+  dq[0] = int4_decode_sixteenth<0>(c[0], hi); dq[1] = int4_decode_sixteenth<1>(c[0], hi);
+  dq[2] = int4_decode_sixteenth<2>(c[0], hi); dq[3] = int4_decode_sixteenth<3>(c[0], hi);
+  dq[4] = int4_decode_sixteenth<4>(c[0], hi); dq[5] = int4_decode_sixteenth<5>(c[0], hi);
+  dq[6] = int4_decode_sixteenth<6>(c[0], hi); dq[7] = int4_decode_sixteenth<7>(c[0], hi);
+  return s * 16.0f;
 }
 
 template <bool BF16>
@@ -315,7 +315,12 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
   constexpr bool WRITE = RED != RED_ATOMIC && RED != RED_TILE;   // the first pass of a two-pass group writes nothing
   const bool any = ACC == ACC_FULL || nvalid > 0;
 
-  float g[8], m[8], v[8], w[8];
+  // A bf16 scale has 8 significant bits and a decoded code at most 4, so dec(c) * s is exact in fp32 (also where
+  // it is subnormal: its lowest bit is at least 2^-142) and theta~ = w - u and e = theta~ - dec(c') s' may be
+  // formed by one fused multiply-add each: the same real number is rounded once either way.  Until then w holds
+  // the decoded values and sc the factor.
+  constexpr bool EXACT_SCALE = SCALE_BF16 && !MASTER;
+  float g[8], m[8], v[8], w[8], sc = 1.0f;
   load_bf16x8<ACC>(static_cast<const uint16_t *>(td.g) + e0, nvalid, g);
   load_state8<STATE_BF16, ACC>(td.m, e0, nvalid, m);
   if (ADAM) load_state8<STATE_BF16, ACC>(td.v, e0, nvalid, v);
@@ -325,7 +330,11 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
     uint32_t c[2];
     load_codes8<FMT, ACC>(td.w, e0, nvalid, c);
     const float s_old = any ? load_scale<SCALE_BF16>(td.s, sg) : 0.0f;
-    dequant8<FMT>(c, s_old, w);
+    sc = decode8<FMT>(c, s_old, w);
+    if (!EXACT_SCALE) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) w[j] *= sc;
+    }
   }
 
   __builtin_amdgcn_s_setprio(0);      // loads issued: back to the default priority (see eco_step_kernel)
@@ -351,25 +360,40 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
       for (int j = 0; j < 8; ++j) eta[j] = a.c1 / d[j];
     }
   }
-  if (a.wd != 0.0f) {
-    // decoupled decay; off in most runs, so it is kept a (wave-uniform) branch: the empty asm statement
-    // stops the compiler from turning the block into eight multiply-subtract-select triples
-    asm volatile("" ::: "memory");
-#pragma unroll
-    for (int j = 0; j < 8; ++j) w[j] = w[j] - a.wd * w[j];
-  }
+  float u[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    float u;
     if (ADAM) {
-      u = eta[j] * m[j];
+      u[j] = eta[j] * m[j];
     } else {
       m[j] = fmaf(a.b1, m[j], a.omb1 * g[j]);
       d[j] = 0.0f;
-      u = a.lr * m[j];
+      u[j] = a.lr * m[j];
     }
-    th[j] = w[j] - u;
-    if (ACC != ACC_FULL && j >= nvalid) th[j] = 0.0f;
+  }
+  // decoupled decay is off in most runs, so it is kept a (wave-uniform) branch: the empty asm statements stop
+  // the compiler from turning the blocks into multiply-subtract-select triples
+  if (EXACT_SCALE && a.wd == 0.0f) {
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < 8; ++j) th[j] = fmaf(w[j], sc, -u[j]);
+  } else {
+    if (EXACT_SCALE) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) w[j] *= sc;
+    }
+    if (a.wd != 0.0f) {
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < 8; ++j) w[j] = w[j] - a.wd * w[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) th[j] = w[j] - u[j];
+  }
+  if (ACC != ACC_FULL) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j >= nvalid) th[j] = 0.0f;
   }
 
   // ECO_QUANTIZE
@@ -409,7 +433,7 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
     if (ALGO == ALGO_SGDM_EXACT) load_f32x8<ACC>(static_cast<const float *>(td.aux) + e0, nvalid, eo);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float e = th[j] - qn[j] * s_new;
+      const float e = SCALE_BF16 ? fmaf(-qn[j], s_new, th[j]) : th[j] - qn[j] * s_new;   // exact product, see above
       if (ALGO == ALGO_ADAM) m[j] = fmaf(a.kappa * d[j], e, m[j]);
       else if (ALGO == ALGO_SGDM) m[j] = fmaf(a.alpha, e, m[j]);
       else { m[j] = fmaf(-a.inv_lr_beta, e, fmaf(a.inv_lr, eo[j], m[j])); eo[j] = e; }
@@ -482,7 +506,7 @@ __device__ __forceinline__ int valid_from(uint64_t e0, uint64_t end) {
 
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(WG_THREADS) void eco_step_ragged_kernel(const StepArgs a) {
-  const TensorDesc td = load_tensor_desc(a, load_table(a.ragged_tensor, blockIdx.x));
+  const TensorDesc td = load_tensor_desc(a, load_table(a.ragged_tensor, blockIdx.x + a.unit_base));
   const uint64_t e0 = td.numel / TILE_ELEMS * TILE_ELEMS + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
   const bool writer = (threadIdx.x & ((1u << (td.bs_shift - 3)) - 1u)) == 0;
   step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_GUARDED, RED_BLOCK>(a, td, e0, valid_from(e0, td.numel),
@@ -494,8 +518,9 @@ __global__ __launch_bounds__(WG_THREADS) void eco_step_ragged_kernel(const StepA
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
   __builtin_amdgcn_s_setprio(3);      // as in eco_step_kernel: loading waves first
-  const TensorDesc td = load_tensor_desc(a, load_table(a.wide_tensor, blockIdx.x));
-  const uint64_t grp = blockIdx.x - td.first_unit;
+  const uint32_t unit = blockIdx.x + a.unit_base;
+  const TensorDesc td = load_tensor_desc(a, load_table(a.wide_tensor, unit));
+  const uint64_t grp = unit - td.first_unit;
   const uint64_t start = grp * td.group_size;
   const uint64_t end = start + td.group_size < td.numel ? start + td.group_size : td.numel;
   const uint64_t e0 = start + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
@@ -515,10 +540,11 @@ __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, int RED>
 __global__ __launch_bounds__(WG_THREADS) void eco_step_tensorwise_kernel(const StepArgs a) {
   __builtin_amdgcn_s_setprio(3);      // as in eco_step_kernel: loading waves first
-  const TensorDesc td = load_tensor_desc(a, load_table(a.tw_tile_tensor, blockIdx.x));
-  const uint64_t tile_off = (uint64_t)(blockIdx.x - td.first_unit) * TILE_ELEMS;
+  const uint32_t unit = blockIdx.x + a.unit_base;
+  const TensorDesc td = load_tensor_desc(a, load_table(a.tw_tile_tensor, unit));
+  const uint64_t tile_off = (uint64_t)(unit - td.first_unit) * TILE_ELEMS;
   const uint64_t e0 = tile_off + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
-  uint32_t *slot = RED == RED_TILE ? a.tile_max + blockIdx.x : a.slots + td.slot;
+  uint32_t *slot = RED == RED_TILE ? a.tile_max + unit : a.slots + td.slot;
   if (tile_off + TILE_ELEMS <= td.numel)
     step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED>(a, td, e0, 8, 0, false, slot);
   else
@@ -528,7 +554,7 @@ __global__ __launch_bounds__(WG_THREADS) void eco_step_tensorwise_kernel(const S
 constexpr int TW_REDUCE_THREADS = 1024;
 template <int FMT>   // a template only so that every translation unit may hold its own copy
 __global__ __launch_bounds__(TW_REDUCE_THREADS) void eco_tensorwise_reduce_kernel(const StepArgs a) {
-  const TensorDesc td = load_tensor_desc(a, a.tw_tensor[blockIdx.x]);
+  const TensorDesc td = load_tensor_desc(a, a.tw_tensor[blockIdx.x + a.unit_base]);
   const uint64_t ntiles = (td.numel + TILE_ELEMS - 1) / TILE_ELEMS;
   const uint32_t *tm = a.tile_max + td.first_unit;
   uint32_t r = 0;
@@ -545,7 +571,7 @@ __global__ __launch_bounds__(TW_REDUCE_THREADS) void eco_tensorwise_reduce_kerne
 
 template <int FMT, bool SCALE_BF16>
 __global__ __launch_bounds__(WG_THREADS) void eco_tensorwise_scale_kernel(const StepArgs a) {
-  const uint32_t i = blockIdx.x * WG_THREADS + threadIdx.x;
+  const uint32_t i = (blockIdx.x + a.unit_base) * WG_THREADS + threadIdx.x;
   if (i >= a.num_tw_tensors) return;
   const TensorDesc td = load_tensor_desc(a, a.tw_tensor[i]);
   float s_new, inv;
@@ -565,29 +591,52 @@ inline unsigned lds_cap(unsigned bytes) { return bytes < 65536u ? bytes : 65536u
     if (launch_err_ != hipSuccess) return launch_err_;                                                            \
   } while (0)
 
+// One work item per workgroup, `units` of them: as many launches as the limit on the threads of one launch asks
+// for (the runtime wants grid x block below 2^32), each told where it starts through StepArgs::unit_base.
+template <class Kernel>
+hipError_t launch_in_chunks(Kernel kernel, uint64_t units, unsigned block, unsigned lds, hipStream_t stream, StepArgs args) {
+  const uint64_t per_launch = args.max_launch_threads / block ? args.max_launch_threads / block : 1;
+  for (uint64_t base = 0; base < units; base += per_launch) {
+    args.unit_base = static_cast<uint32_t>(base);
+    const uint64_t n = units - base < per_launch ? units - base : per_launch;
+    ECO_LAUNCH_CHECKED(kernel, dim3(static_cast<unsigned>(n)), dim3(block), lds, stream, args);
+  }
+  return hipSuccess;
+}
+#define ECO_CHUNKS_CHECKED(...)                                  \
+  do {                                                           \
+    const hipError_t chunk_err_ = launch_in_chunks(__VA_ARGS__); \
+    if (chunk_err_ != hipSuccess) return chunk_err_;             \
+  } while (0)
+
+// The full-tile kernels loop over tiles with the grid as stride, so they take one launch with a capped grid.
+inline unsigned capped_grid(unsigned grid, const StepArgs &args) {
+  const uint64_t most = args.max_launch_threads / WG_THREADS ? args.max_launch_threads / WG_THREADS : 1;
+  return grid > most ? static_cast<unsigned>(most) : grid;
+}
+
 template <int FMT, bool STATE_BF16, bool SC, int RD, int AL>
 hipError_t launch_step_kernels(const StepArgs &args, unsigned grid, hipStream_t stream) {
   if (args.num_tiles)
-    ECO_LAUNCH_CHECKED((eco_step_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(grid), dim3(WG_THREADS), args.lds_bytes, stream, args);
+    ECO_LAUNCH_CHECKED((eco_step_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(capped_grid(grid, args)), dim3(WG_THREADS),
+                       args.lds_bytes, stream, args);
   if (args.num_ragged)
-    ECO_LAUNCH_CHECKED((eco_step_ragged_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_ragged), dim3(WG_THREADS), 0,
-                       stream, args);
+    ECO_CHUNKS_CHECKED((eco_step_ragged_kernel<FMT, STATE_BF16, SC, AL, RD>), args.num_ragged, WG_THREADS, 0, stream, args);
   for (int nw = 1; nw <= MAX_WIDE_WAVES; ++nw) {
     if (!args.num_wide[nw]) continue;
     StepArgs wa = args;
     wa.wide_tensor = args.wide_base + args.wide_offset[nw];
-    ECO_LAUNCH_CHECKED((eco_step_wide_kernel<FMT, STATE_BF16, SC, AL, RD>), dim3(args.num_wide[nw]), dim3(64 * nw),
+    ECO_CHUNKS_CHECKED((eco_step_wide_kernel<FMT, STATE_BF16, SC, AL, RD>), args.num_wide[nw], 64 * nw,
                        lds_cap(args.lds_bytes_wave * nw), stream, wa);
   }
   if (args.num_tw_tiles) {
-    ECO_LAUNCH_CHECKED((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_TILE>), dim3(args.num_tw_tiles),
-                       dim3(WG_THREADS), args.lds_bytes_tw, stream, args);
-    ECO_LAUNCH_CHECKED((eco_tensorwise_reduce_kernel<FMT>), dim3(args.num_tw_tensors), dim3(TW_REDUCE_THREADS), 0, stream,
-                       args);
-    ECO_LAUNCH_CHECKED((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_SLOT>), dim3(args.num_tw_tiles),
-                       dim3(WG_THREADS), args.lds_bytes_tw, stream, args);
-    ECO_LAUNCH_CHECKED((eco_tensorwise_scale_kernel<FMT, SC>), dim3((args.num_tw_tensors + WG_THREADS - 1) / WG_THREADS),
-                       dim3(WG_THREADS), 0, stream, args);
+    ECO_CHUNKS_CHECKED((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_TILE>), args.num_tw_tiles, WG_THREADS,
+                       args.lds_bytes_tw, stream, args);
+    ECO_CHUNKS_CHECKED((eco_tensorwise_reduce_kernel<FMT>), args.num_tw_tensors, TW_REDUCE_THREADS, 0, stream, args);
+    ECO_CHUNKS_CHECKED((eco_step_tensorwise_kernel<FMT, STATE_BF16, SC, AL, RD, RED_SLOT>), args.num_tw_tiles, WG_THREADS,
+                       args.lds_bytes_tw, stream, args);
+    ECO_CHUNKS_CHECKED((eco_tensorwise_scale_kernel<FMT, SC>), (args.num_tw_tensors + WG_THREADS - 1) / WG_THREADS, WG_THREADS,
+                       0, stream, args);
   }
   return hipSuccess;
 }

@@ -138,6 +138,11 @@ def test_flat_helpers_validate(eco):
     assert q(bs=0) == eco.ECO_EINVAL
     assert q(src=0x1004) == eco.ECO_EALIGN
     assert q(n=(1 << 40) + 1) == eco.ECO_EUNSUPPORTED          # size guard, before any launch
+    assert q(n=1 << 35) == eco.ECO_EUNSUPPORTED                # one launch holds fewer than 2^32 threads: 2^26 tiles are one too many
+    assert q(n=1 << 35, bs=1 << 36) == eco.ECO_EUNSUPPORTED    # the same for one scale over the tensor
+    assert q(n=1 << 35, bs=520) == eco.ECO_EUNSUPPORTED        # wide groups: a workgroup of two waves for every 520 elements
+    assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 1 << 35, 0, 128, 0, 0x3000, 0) == eco.ECO_EUNSUPPORTED
+    assert _status(eco, eco.eco_bandwidth_probe, 0, 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1 << 35, 0) == eco.ECO_EINVAL
     assert q(bs=8200, n=1 << 20) == eco.ECO_EUNSUPPORTED       # wide groups end at 8192 elements ...
     assert q(bs=20, n=1 << 20) == eco.ECO_EUNSUPPORTED         # ... and are multiples of 8
     assert _status(eco, eco.eco_dequantize, 0x1000, 0x2000, 1024, 0, 128, 0, None, 0) == eco.ECO_EINVAL
@@ -154,6 +159,10 @@ def test_flat_helpers_validate(eco):
     assert _status(eco, eco.eco_set_option, 5, 1) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_set_option, 0, 100000) == eco.ECO_EINVAL
     assert _status(eco, eco.eco_set_option, 2, 40000) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_set_option, 3, 100) == eco.ECO_EINVAL
+    assert _status(eco, eco.eco_set_option, 3, 2 ** 32) == eco.ECO_EINVAL
+    eco.eco_set_option(3, 4096)
+    eco.eco_set_option(3, -1)
     eco.eco_set_option(0, 0)
     eco.eco_set_option(2, -1)
 

@@ -179,3 +179,75 @@ def test_config4_other_modes_sampled(variant):
               "sgdm-exact": dict(opt=eco.ECO_OPT_SGDM, mode=eco.ECO_MODE_EXACT)}[variant]
     n = run_fullsize(workloads.config4(), steps=2, n_tensors=12, seed=17, layout=layout)
     assert n > 300_000
+
+
+# ------------------------------------------------------------------ one tensor at the largest sizes
+CHUNK = 1 << 28
+
+
+def _one_huge_tensor(eco, o32, numel, fmt, state_bf16, span_edges, seed):
+    """One block-scaled tensor of `numel` elements, set up chunk by chunk (the initial quantizer is local to a
+    scale block, so quantizing slices of whole blocks is quantizing the tensor), stepped once through the
+    plan-less entry point; the oracle recomputes the spans [e0, e1) from the inputs the device held."""
+    sdt = torch.bfloat16 if state_bf16 else torch.float32
+    dt = eco.ECO_DT_BF16 if state_bf16 else eco.ECO_DT_FP32
+    need = numel * ((1 if fmt == 0 else 0.5) + 2 + 2 * (2 if state_bf16 else 4)) + numel // 128 * 4 + (6 << 30)
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < need:
+        pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory, {free / 2**30:.0f} GiB are free")
+    codes = torch.empty(numel if fmt == 0 else numel // 2, dtype=torch.uint8, device=DEV)
+    scales = torch.empty((numel + 127) // 128, dtype=sdt, device=DEV)
+    grad = torch.empty(numel, dtype=torch.bfloat16, device=DEV)
+    m = torch.empty(numel, dtype=sdt, device=DEV)
+    v = torch.empty(numel, dtype=sdt, device=DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    for off in range(0, numel, CHUNK):
+        n = min(CHUNK, numel - off)
+        src = torch.randn(n, device=DEV, generator=gen) * 0.02
+        eco.eco_quantize_init(src, eco.ECO_DT_FP32, n, fmt, 128, dt, codes[off if fmt == 0 else off // 2:], scales[off // 128:])
+        m[off:off + n] = (torch.randn(n, device=DEV, generator=gen) * 1e-3).to(sdt)
+        v[off:off + n] = (torch.rand(n, device=DEV, generator=gen) * 1e-5).to(sdt)
+        grad[off:off + n] = (torch.randn(n, device=DEV, generator=gen) * 2e-3).to(torch.bfloat16)
+        torch.cuda.synchronize()
+        del src
+        if off % (16 * CHUNK) == 0:
+            print(f"[huge] filled {off + n} of {numel}", flush=True)
+
+    def grab(e0, e1):
+        c = codes[e0:e1] if fmt == 0 else codes[e0 // 2:(e1 + 1) // 2]
+        return dict(codes=c.cpu().numpy().copy(), scales=to_f32(scales[e0 // 128:(e1 + 127) // 128]), grad=bf16_bits(grad[e0:e1]),
+                    m=to_f32(m[e0:e1]), v=to_f32(v[e0:e1]))
+
+    hp = eco.make_hparams(block_size=128, state_dtype=dt, scale_dtype=dt, lr=1e-3, step=3, seed=seed)
+    before = [grab(e0, e1) for e0, e1 in span_edges]
+    print(f"[huge] stepping {numel} elements", flush=True)
+    eco.eco_step_tensors([eco.make_tensor(codes, scales, grad, m, v, numel, 11, fmt)], hp)
+    torch.cuda.synchronize()
+    for (e0, e1), h in zip(span_edges, before):
+        oracle_step(o32, h, e1 - e0, step_config(hp, 11, fmt, elem_offset=e0, group_size=128))
+        after = grab(e0, e1)
+        after["grad"] = h["grad"]
+        st = compare(after, h, f"elements [{e0}, {e1}) of {numel}", state_bf16)
+        assert st["code_mismatch"] == 0
+    assert all_finite(m) and all_finite(v)
+    del codes, scales, grad, m, v
+    torch.cuda.empty_cache()
+
+
+def test_one_fp8_tensor_of_more_than_2_pow_32_elements():
+    """Element indices beyond 32 bits in the FP8 / fp32-state kernel and its ragged tail."""
+    from paper_2601_22101_amd import binding as eco
+    n = (1 << 32) + 3 * 512 + 100
+    _one_huge_tensor(eco, oracle.get("f32"), n, 0, False,
+                     [(0, 6144), ((1 << 31) - 3072, (1 << 31) + 3072), ((1 << 32) - 3072, n)], seed=32)
+
+
+def test_one_int4_tensor_of_more_than_2_pow_35_elements():
+    """The largest plan 288 GB hold (INT4 codes, bf16 scales, gradient and state: 6.5 bytes per element): more tiles than
+    one launch can take workgroups, and random-number counters (element index / 8) beyond 32 bits."""
+    from paper_2601_22101_amd import binding as eco
+    n = (1 << 35) + 3 * 512 + 100
+    _one_huge_tensor(eco, oracle.get("f32"), n, 1, True,
+                     [(0, 6144), ((1 << 32) - 3072, (1 << 32) + 3072), ((1 << 35) - 3072, n)], seed=35)

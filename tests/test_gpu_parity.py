@@ -420,6 +420,34 @@ def test_results_do_not_depend_on_launch_geometry_or_plan_order(harness, eco):
     assert _equal(results[0], results[1]) and _equal(results[0], results[2])
 
 
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
+def test_a_step_launched_in_chunks_gives_the_same_results(harness, eco, fmt):
+    """A launch may hold fewer than 2^32 threads, so very large plans are stepped in several launches per kernel
+    (and the full-tile kernel loops).  A small limit set from the host makes a small plan take that path: every
+    class of scale group, ragged tails and unquantized tensors, several tensor-wise tensors of several tiles."""
+    T = workloads.TensorSpec
+    ts = [T("blocks", (96, 1024), fmt), T("ragged_a", (4097,), fmt), T("ragged_b", (12345,), fmt), T("ragged_c", (100,), fmt),
+          T("rows_2w", (40, 1000), fmt, granularity="row"), T("rows_4w", (37, 2048), fmt, granularity="row"),
+          T("rows_16w", (9, 8192), fmt, granularity="row"), T("whole_a", (70000,), fmt, granularity="tensor"),
+          T("whole_b", (8193,), fmt, granularity="tensor"), T("whole_c", (3 * 65536,), fmt, granularity="tensor"),
+          T("norm", (5000,), "bf16_plain"), T("norm_b", (700,), "bf16_plain"), T("norm_c", (513,), "bf16_plain")]
+    wl = workloads.Workload("chunks_" + fmt, ts, steps=3)
+    results = []
+    for limit in (-1, 1024, 2048 + 1024):
+        eco.eco_set_option(3, limit)
+        try:
+            dw = harness.DeviceWorkload(wl, DEV)
+            for k in (1, 2, 3):
+                dw.fill_gradients(k)
+                dw.step(k)
+            torch.cuda.synchronize()
+            results.append(_snapshot(dw))
+            dw.close()
+        finally:
+            eco.eco_set_option(3, -1)
+    assert _equal(results[0], results[1]) and _equal(results[0], results[2])
+
+
 def _random_plan(rng, fmt):
     """A random tensor list for one plan: awkward and boundary sizes, every class of scale group."""
     T = workloads.TensorSpec
