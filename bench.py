@@ -292,6 +292,87 @@ def time_launches(fn, reps: int, warm: int = 2):
     return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
 
 
+def address_map(torch, workloads, eco, harness) -> int:
+    """Where the arrays of the step lie in device memory, and what that does to it.  One allocation of most of the
+    device's memory; (1) the library's byte-mix probe (the loads and stores of the FP8 / fp32-state Adam step on 2^30
+    elements, no arithmetic) with codes, scales, gradient and m packed at R GiB into the allocation and v moved through it
+    in steps of 4 GiB; (2) the step itself on configuration 4 with its arenas packed at the start of the allocation, and
+    with only the v arena moved to the start of every 32 GiB region.  Prints the tables; the last line is JSON."""
+    GiB, MiB = 1 << 30, 1 << 20
+    free = torch.cuda.mem_get_info()[0]
+    pool_gib = min(244, int((free - (12 << 30)) // (4 * GiB) * 4))
+    pool = torch.zeros(pool_gib * GiB, dtype=torch.uint8, device="cuda:0")
+    base = pool.data_ptr()
+    numel = 1 << 30
+    size = dict(codes=1 * GiB, scales=32 * MiB, grad=2 * GiB, m=4 * GiB, v=4 * GiB)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    def probe(at):
+        for k, p in at.items():
+            assert 0 <= p and p + size[k] <= pool_gib * GiB, (k, p)
+        a = {k: base + p for k, p in at.items()}
+        for i in range(4):                        # one warm-up launch, three timed ones; the best counts
+            eco.eco_bandwidth_probe(0, a["codes"], a["scales"], a["grad"], a["m"], a["v"], numel)
+            ev[i].record()
+        torch.cuda.synchronize()
+        return numel * BYTES_PER_PARAM["fp8"] / min(ev[i].elapsed_time(ev[i + 1]) for i in range(3)) / 1e6
+
+    print(f"one allocation of {pool_gib} GiB; byte-mix probe on 2^30 elements, GB/s of algorithmic traffic / 10;", flush=True)
+    print("codes, scales, gradient, m packed from R GiB on (7 GiB); columns: v at 0, 4, 8, ... GiB ('.' = overlap)", flush=True)
+    table = {}
+    for R in range(0, pool_gib - 8, 32):
+        row = []
+        for g in range(0, pool_gib - 4, 4):
+            if g < R + 8 and g + 4 > R:
+                row.append(None)
+                continue
+            at = dict(codes=R * GiB, scales=(R + 1) * GiB, grad=(R + 1) * GiB + 32 * MiB, m=(R + 3) * GiB + 32 * MiB, v=g * GiB)
+            row.append(probe(at))
+        table[R] = row
+        print("R=%3d: %s" % (R, " ".join("   ." if x is None else "%4.0f" % (x / 10) for x in row)), flush=True)
+    # regions (32 GiB) in which v is slow, for every R: the kinds of region show as identical rows
+    slow = {}
+    for R, row in table.items():
+        vals = [x for x in row if x is not None]
+        cut = (min(vals) + max(vals)) / 2
+        per_region = {}
+        for i, x in enumerate(row):
+            if x is not None:
+                per_region.setdefault(i * 4 // 32, []).append(x < cut)
+        slow[R] = [r for r, flags in sorted(per_region.items()) if sum(flags) * 2 > len(flags)]
+        print(f"rest in region {R // 32}: v is slow in regions {slow[R]}", flush=True)
+
+    wl = workloads.CONFIGS[4]()
+    steps = {}
+    packed_v_gib = None
+    for v_gib in [None] + list(range(32, pool_gib - 13, 32)):
+        skew = {}
+        if v_gib is not None:
+            skew["v"] = (int((v_gib - packed_v_gib) * GiB) >> 21) << 21
+        dw = harness.DeviceWorkload(wl, "cuda:0", init="bulk", single_allocation=pool, skew_bytes=skew, grad_sets=1)
+        dw.fill_gradients_bulk(1, 0)
+        torch.cuda.synchronize()
+        at = {k: round((getattr(dw, k).data_ptr() - base) / GiB, 1) for k in ("codes", "grad", "m", "v")}
+        if v_gib is None:
+            packed_v_gib = (dw.v.data_ptr() - base) / GiB
+        kk = [0]
+
+        def one():
+            kk[0] += 1
+            dw.step(kk[0], 0)
+        avg, med, mn = time_launches(one, 5, warm=2)
+        steps[at["v"]] = med
+        print(f"configuration 4, the step itself: codes at {at['codes']}, gradient at {at['grad']}, m at {at['m']}, v at {at['v']} GiB: "
+              f"median {med:.3f} ms = {100 * algorithmic_bytes(wl) / med / 1e6 / HBM_PEAK_GBS:.1f} % of peak", flush=True)
+        dw.close()
+        del dw
+    print(json.dumps({"address_map": {"pool_gib": pool_gib, "probe_gbs_by_R_and_v": {str(R): [None if x is None else round(x) for x in row]
+                                                                                       for R, row in table.items()},
+                                      "slow_regions_of_v_by_R": {str(R): v for R, v in slow.items()},
+                                      "step_ms_by_v_gib": steps}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -311,11 +392,13 @@ def main() -> int:
     ap.add_argument("--granularity", default="block", choices=["block", "row", "tensor"],
                     help="scale groups of the quantized tensors: the configuration's 128-element blocks (headline), "
                          "one scale per row (the paper's FP8 runs) or per tensor (its INT4 run)")
-    ap.add_argument("--placement", default="auto", choices=["auto", "packed", "spread", "dense", "dense-default"],
+    ap.add_argument("--placement", default="auto", choices=["auto", "packed", "spread", "dense", "dense-default", "probed"],
                     help="where the harness puts the arenas in HBM: one allocation per arena (packed); one allocation without "
-                         "gaps, m first and v last with codes, scales and gradients between them (dense; auto = dense for "
-                         "workloads of 8 GiB and more) or in the order codes, scales, gradients, m, v (dense-default); one "
-                         "allocation with the codes+gradient, m and v arenas tens of GiB of unused memory apart (spread)")
+                         "gaps, m first and v last with codes, scales and gradients between them (dense) or in the order codes, "
+                         "scales, gradients, m, v (dense-default); one allocation without gaps, m first and v after as many of "
+                         "the other arenas as the library's bandwidth probe finds fastest at set-up (probed; auto = probed for "
+                         "FP8 / fp32-state workloads of 8 GiB and more, dense for other large ones); one allocation with the "
+                         "codes+gradient, m and v arenas tens of GiB of unused memory apart (spread)")
     ap.add_argument("--spread-gap-gib", type=int, default=0, help="distance between the arena groups of the spread placement (0 = default)")
     ap.add_argument("--calibrate-gaps", type=int, default=3,
                     help="spread placement: time this many candidate distances (the default and smaller ones, 8 GiB apart) "
@@ -323,7 +406,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true", help="skip the untimed parity step after the timed region")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the copy-kernel ceilings after the timed region")
-    ap.add_argument("--compare-placements", default="packed,spread",
+    ap.add_argument("--compare-placements", default="dense,packed,spread",
                     help="comma-separated placements to time the same step on after the headline run (configuration 4, "
                          "headline variant only; empty = none)")
     ap.add_argument("--bulk-grad", action="store_true",
@@ -335,6 +418,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed steps, run two plain 1 GiB device copies (a reference of known size for "
                          "scaling rocprofv3 byte counters)")
+    ap.add_argument("--address-map", action="store_true",
+                    help="instead of the benchmark: time the library's bandwidth probe, and the step itself, with the arrays "
+                         "placed by hand in one large allocation, and print where in it they get in each other's way")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -347,6 +433,9 @@ def main() -> int:
     import workloads
     from paper_2601_22101_amd import binding as eco
     from paper_2601_22101_amd import harness
+
+    if args.address_map:
+        return address_map(torch, workloads, eco, harness)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -427,6 +516,7 @@ def main() -> int:
         "config": {"workload": wl.name, "granularity": args.granularity, "tensors": len(wl.tensors), "parameters": wl.numel,
                    "placement": dw.placement,
                    "placement_probe_gib_ms": dw.calibration,
+                   "placement_probe": dw.probe_results,
                    "format": ("fp8_e4m3 codes, %s fp32 scales, bf16 gradients, fp32 m and v"
                               if args.config != 5 else "int4 codes, %s bf16 scales, bf16 gradients, bf16 m and v")
                    % {"block": "block-128", "row": "row-wise", "tensor": "tensor-wise"}[args.granularity],

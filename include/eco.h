@@ -48,9 +48,12 @@
  *
  * Performance notes for callers (MI355X; none of this changes results)
  *  - The step is bound by HBM bandwidth (the INT4 / bf16-state form by vector-ALU issue) and runs at the rate
- *    of a plain copy kernel on the same arrays.  The arrays of a tensor are streamed in lock-step; where they
- *    lie in device memory relative to each other (packed, or tens of GiB apart) moves the step time by about
- *    one per cent, less than the difference between two processes.
+ *    of a plain copy kernel on the same arrays.  The arrays of a tensor are streamed in lock-step, and where they
+ *    lie in device memory relative to each other matters by 2-3 per cent of the step (9 per cent of its memory
+ *    traffic alone): measured inside one allocation of most of the memory, the address space falls into 32 GiB
+ *    regions of three kinds, and the step is at its best when m or v lies in a region of another kind than the
+ *    other arrays.  Which region is of which kind depends on the physical addresses an allocation gets;
+ *    eco_bandwidth_probe, timed on candidate addresses before anything is stored there, tells.
  *  - One plan over all tensors of a model is one kernel launch per storage format; per-tensor calls pay a
  *    launch each.
  *  - Tensor lengths that are multiples of 512 keep every tile on the unguarded fast path.
@@ -244,7 +247,8 @@ eco_status_t eco_philox_fill(uint64_t seed, uint64_t step, uint32_t tensor_id, u
 
 /*
  * eco_bandwidth_probe — measurement aid, not part of the method: what the memory system delivers for the step's
- * access pattern with the arithmetic taken out (the ceiling a step can be compared with).
+ * access pattern with the arithmetic taken out (the ceiling a step can be compared with; and, timed on candidate
+ * addresses before anything is stored there, a way to choose where the arrays should lie, see the performance notes).
  *   kind 0: byte-mix copy.  Every lane loads what a lane of the FP8 / fp32-state Adam step loads for its 8 elements
  *           (codes, gradient, m, v, the 128-block's scale) and stores what it stores, same tile geometry and
  *           occupancy cap: 11.03 B read + 9.03 B written per element.  codes: numel bytes, scales: numel/128 fp32,

@@ -41,13 +41,18 @@ class DeviceWorkload:
     kind) so that a multi-thousand-tensor model costs a handful of allocations; each tensor still
     has its own descriptor in the plan and its own, 256-byte aligned, slices."""
 
-    # Streams that advance in lock-step (the m, v and master/error arrays, and the codes + gradient pair)
-    # run 5-8 % faster on MI355X when they lie in different 32 GiB regions of one device allocation than
-    # when they are packed next to each other (measured: 70 -> 76 % of peak HBM bandwidth for the Adam
-    # step on 3.3 B parameters; gaps of 24-64 GiB between the groups all give the gain).  The "spread"
-    # placement therefore puts the arena groups SPREAD_GAP bytes apart inside a single allocation; the
-    # gaps are address space and memory the benchmark does not use (a training framework would keep
-    # other data there).
+    # Where the arrays lie in device memory matters on MI355X: measured with the arrays placed by hand inside one
+    # 244 GiB allocation, the address space falls into 32 GiB regions of three kinds, and the step (nine streams
+    # that advance in lock-step) runs 3 % faster, its loads and stores alone 9 % faster, when the m or the v
+    # array lies in a region of another kind than the rest; a plain two-stream copy does not care.  Which region
+    # is of which kind is a property of the physical addresses an allocation happens to get.  Placements:
+    #   "packed"  one allocation per arena, wherever the allocator puts them;
+    #   "dense"   one allocation, no byte unused, order m | codes, scales, gradients | v;
+    #   "probed"  one allocation, no byte unused; m first, and v after as many of the other arenas (codes and scales,
+    #             then the gradient arenas) as the library's bandwidth probe, run on the candidate addresses before
+    #             anything is initialised, finds fastest;
+    #   "spread"  one allocation with the arena groups SPREAD_GAP bytes apart: the gaps are memory the benchmark
+    #             does not use (kept for comparison).
     SPREAD_GAP = 48 << 30
     SPREAD_MIN_BYTES = 8 << 30          # "auto" spreads workloads of at least this footprint
 
@@ -58,9 +63,9 @@ class DeviceWorkload:
         """`layout`: hyper-parameter overrides that are fixed for the life of the plan (opt, mode, ...).
         In the master-weight mode the fp32 initial weights are kept as the master copy; in the
         exact-injection mode the aux buffer starts as e_0 = theta_0 - q(theta_0) (Appendix A).
-        `placement`: "packed" = one allocation per arena (wherever the allocator puts them), "spread" = one
-        allocation with the arena groups far apart (see SPREAD_GAP), "auto" = spread for large workloads when
-        the device has the memory for it.  `skew_bytes` / `single_allocation` place arenas by hand (probes).
+        `placement`: "packed", "dense", "probed" or "spread" (see the class comment); "auto" = probed for large
+        workloads the probe's byte mix fits (FP8 codes, block-wise fp32 scales, fp32 state, Adam), dense for other
+        large ones, packed for small ones.  `skew_bytes` / `single_allocation` place arenas by hand (probes).
         `order`: "default" lays the arenas out as codes, scales, gradients, m, v; "state-apart" (one allocation only)
         puts m first and v last with everything else between them, no byte unused.
         `grad_sets`: number of gradient arenas (each with a plan of its own over the same weights and state),
@@ -83,9 +88,13 @@ class DeviceWorkload:
         dev = self.device
         skew = dict(skew_bytes or {})
         self.placement = "packed"
+        self._arena_order = None
+        self.probe_results = None
+        large = self.pool_bytes(wl, self.mode, grad_sets) >= self.SPREAD_MIN_BYTES and dev.type == "cuda"
         if placement == "auto":
-            # large workloads: one allocation without gaps, m first and v last (as fast as the spread placement, measured)
-            placement = "dense" if self.pool_bytes(wl, self.mode, grad_sets) >= self.SPREAD_MIN_BYTES and dev.type == "cuda" else "packed"
+            placement = ("probed" if self._probe_fits() else "dense") if large else "packed"
+        if placement == "probed" and not (dev.type == "cuda" and self._probe_fits()):
+            placement = "dense"
         if placement == "spread" and not skew and single_allocation is False and dev.type == "cuda":
             need = self.pool_bytes(wl, self.mode, grad_sets)
             ngaps = 3 if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER) else 2
@@ -98,12 +107,13 @@ class DeviceWorkload:
                     skew["aux"] = gap
                 single_allocation = True
                 self.placement = f"one allocation, arena groups {gap >> 30} GiB apart"
-        if placement in ("dense", "dense-default") and single_allocation is False and not skew:
+        probe_order = placement == "probed" and single_allocation is False and not skew
+        if placement in ("dense", "dense-default", "probed") and single_allocation is False and not skew:
             single_allocation = True
-            if placement == "dense":
+            if placement != "dense-default":
                 self.order = "state-apart"
             self.placement = ("one allocation, no gaps, order: " +
-                              ("m | codes, scales, gradients | v" if placement == "dense" else "codes, scales, gradients, m, v"))
+                              ("m | codes, scales, gradients | v" if placement != "dense-default" else "codes, scales, gradients, m, v"))
         pool_buf, pool_pos = None, 0
         external = isinstance(single_allocation, torch.Tensor)
         if external:                                         # a caller-owned uint8 pool; skew["pool"] = where to start in it
@@ -142,7 +152,9 @@ class DeviceWorkload:
             want += [("m", off, self.state_dtype), ("v", off, self.state_dtype)]
             if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER):
                 want.append(("aux", off, torch.float32))
-            if self.order == "state-apart":
+            if self._arena_order is not None:
+                want.sort(key=lambda w: self._arena_order.index(w[0]))
+            elif self.order == "state-apart":
                 # m first, v last: the two largest arrays of the lock-step streams at the two ends of the footprint,
                 # everything else (codes, scales, gradients of all resident steps) between them
                 want.sort(key=lambda w: {"m": 0, "v": 2, "aux": 3}.get(w[0], 1))
@@ -167,15 +179,75 @@ class DeviceWorkload:
                                                 self.v[o:o + n], None if self.aux is None else self.aux[o:o + n]))
 
         self.calibration = None
+        if probe_order:
+            self._choose_order_by_probe(pool_buf, pool_pos, off, soff, code_bytes, woff, grad_sets)
         if calibrate_gaps > 1 and pool_buf is not None and not external and "GiB apart" in self.placement:
             skew = self._calibrate(build_views, pool_buf, skew, calibrate_gaps)
-        build_views(skew, zero=external or self.calibration is not None)
+        build_views(skew, zero=external or self.calibration is not None or self.probe_results is not None)
         if init == "bulk":
             self.init_weights_bulk()
         elif init:
             self.init_weights()
         self.plans = [eco.Plan([self.descriptor(tv, g) for tv in self.tensors], self.hparams(1)) for g in range(grad_sets)]
         self.plan = self.plans[0]
+
+    def _probe_fits(self) -> bool:
+        """The library's bandwidth probe moves the bytes of the FP8 / fp32-state Adam step with block-128 fp32 scales;
+        it is run on a workload's own arenas only where those are at least as large as what it touches."""
+        wl = self.wl
+        quant = [t for t in wl.tensors if t.fmt in ("fp8", "int4")]
+        return (not wl.state_bf16 and not wl.scale_bf16 and wl.block_size == 128 and len(quant) > 0 and
+                all(t.fmt == "fp8" and t.group_size(128) == 128 for t in quant) and
+                self.mode in (eco.ECO_MODE_ECO, eco.ECO_MODE_NAIVE) and self.layout.get("opt", eco.ECO_OPT_ADAM) == eco.ECO_OPT_ADAM)
+
+    def _choose_order_by_probe(self, pool_buf, pool_pos, off, soff, code_bytes, woff, grad_sets):
+        """Candidate orders of the arenas, none of which leaves a byte unused: m first and v after the first k of the
+        other arenas (codes + scales + unquantized weights as one unit, then the gradient arenas), k = 1 .. all of
+        them; and, mirrored, v last and m before the last k.  The probe is timed on each candidate's addresses in the
+        still uninitialised allocation, and the fastest order is kept."""
+        sizes = {"codes": max(code_bytes, 1), "scales": 4 * max(soff, 1), "plain": 2 * max(woff, 1), "m": 4 * off, "v": 4 * off}
+        grads = ["grad"] + [f"grad_extra{k}" for k in range(1, grad_sets)]
+        for g in grads:
+            sizes[g] = 2 * off
+        fillers = [["codes", "scales", "plain"]] + [[g] for g in grads]
+        numel = min(code_bytes, off) // 1024 * 1024
+        if numel == 0:
+            return
+        F = len(fillers)
+        flat = lambda units: [n for u in units for n in u]
+        orders = [["m"] + flat(fillers[:k]) + ["v"] + flat(fillers[k:]) for k in range(1, F + 1)]
+        orders += [flat(fillers[:F - k]) + ["m"] + flat(fillers[F - k:]) + ["v"] for k in range(1, F)]
+        base = pool_buf.data_ptr()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        results = []
+        for idx, order in enumerate(orders):
+            at, pos = {}, pool_pos
+            for name in order:
+                at[name] = pos
+                pos = _round_up(pos + sizes[name], 1 << 21)
+            assert pos <= pool_buf.numel()
+            a = {n: base + at[n] for n in ("codes", "scales", "grad", "m", "v")}
+            for i in range(3):                      # one warm-up launch, two timed ones
+                eco.eco_bandwidth_probe(0, a["codes"], a["scales"], a["grad"], a["m"], a["v"], numel)
+                ev[i].record()
+            torch.cuda.synchronize(self.device)
+            results.append((min(ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])), idx, at))
+        best_ms, best, at = min(results)
+        self._arena_order = orders[best]
+        gib = lambda x: round((x - pool_pos) / 2**30, 1)
+        self.probe_results = [{"gib_into_the_allocation": {n: gib(at_[n]) for n in ("m", "v", "codes", "grad")},
+                               "probe_gbs": round(numel * 20.0625 / ms / 1e6)} for ms, _, at_ in results]
+        units = ["m" if n == "m" else "v" if n == "v" else "codes, scales" if n == "codes" else "g" for n in orders[best]
+                 if n not in ("scales", "plain")]
+        runs = []                                                # "g g g" -> "3 gradient arenas"
+        for u in units:
+            if u == "g" and runs and runs[-1][0] == "g":
+                runs[-1][1] += 1
+            else:
+                runs.append([u, 1])
+        text = " | ".join(f"{c} gradient arena{'s' if c > 1 else ''}" if u == "g" else u for u, c in runs)
+        self.placement = (f"one allocation, no gaps, order chosen at set-up by the library's bandwidth probe among {len(orders)} "
+                          f"orders: {text}")
 
     def _calibrate(self, build_views, pool_buf, skew, n_candidates):
         """Times the step for the default gap and for smaller ones (steps of 8 GiB, not below 24 GiB) inside

@@ -500,12 +500,16 @@ def test_results_do_not_depend_on_where_the_arenas_lie(harness, eco):
         b.step(k, k - 1)
     torch.cuda.synchronize()
     assert _equal(_snapshot(a), _snapshot(b))
-    # one allocation without gaps, m first and v last (what "auto" chooses for large workloads), and the plain order
-    for placement, first in (("dense", "m"), ("dense-default", "codes")):
+    # one allocation without gaps, m first and v last, and the plain order
+    # ... and the order a bandwidth probe picks at set-up among the gap-free ones (what "auto" chooses for large workloads)
+    for placement, first in (("dense", "m"), ("dense-default", "codes"), ("probed", None)):
         c = harness.DeviceWorkload(wl, DEV, placement=placement, grad_sets=2)
         assert "no gaps" in c.placement
         ptrs = {k: getattr(c, k).data_ptr() for k in ("m", "codes", "scales", "grad", "v")}
-        assert min(ptrs, key=ptrs.get) == first and max(ptrs, key=ptrs.get) == "v"
+        if first is not None:
+            assert min(ptrs, key=ptrs.get) == first and max(ptrs, key=ptrs.get) == "v"
+        else:
+            assert "probe" in c.placement and len(c.probe_results) == 5 and all(r["probe_gbs"] > 0 for r in c.probe_results)
         assert ptrs["v"] + c.v.numel() * 4 - min(ptrs.values()) < 2 * harness.DeviceWorkload.pool_bytes(wl, grad_sets=2)
         for k in (1, 2, 3):
             c.fill_gradients(k, k & 1)
