@@ -14,6 +14,10 @@ namespace eco {
 __device__ __forceinline__ uint32_t f2u(float x) { return __float_as_uint(x); }
 __device__ __forceinline__ float u2f(uint32_t x) { return __uint_as_float(x); }
 
+// Votes over the active lanes of the wave, taken on the comparison's own lane mask.
+__device__ __forceinline__ bool wave_all(bool p) { return __builtin_amdgcn_ballot_w64(p) == __builtin_amdgcn_read_exec(); }
+__device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballot_w64(p) != 0; }
+
 // ---------------------------------------------------------------------------------- bfloat16
 // A bfloat16 is the upper half of an fp32.
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return u2f(packed << 16); }
@@ -92,16 +96,26 @@ constexpr float DIV_MID_N_LO = 0x1p-40f, DIV_MID_N_HI = 0x1p40f;      // numerat
 constexpr uint32_t E4M3_MIN_NORMAL_BITS = 0x3C800000u;     // fp32 bit pattern of 2^-6
 constexpr uint32_t SR_CENTRE = 8u;                         // half of the 2^4 fraction units one random unit is worth
 
+// f + 16 * h modulo 2^32, h = the low (HALF = 0) or high (HALF = 1) 16 bits of a Philox word: the random field of an
+// element, in units of 2^-20 of a grid step.  One v_mad_u32_u16 (u16 x u16 + u32; op_sel picks the half of the word).
+template <int HALF>
+__device__ __forceinline__ uint32_t add_random_field(uint32_t f, uint32_t word) {
+  uint32_t t;
+  if (HALF) asm("v_mad_u32_u16 %0, %1, 16, %2 op_sel:[1,0,0,0]" : "=v"(t) : "v"(word), "v"(f));
+  else asm("v_mad_u32_u16 %0, %1, 16, %2" : "=v"(t) : "v"(word), "v"(f));
+  return t;
+}
+
 // Magnitude code (0..126) of |y|.  NORMAL_ONLY: the caller guarantees |y| >= 2^-6 (the common
-// case, decided once per wave).  ay must be non-negative.
-template <int ROUND, bool NORMAL_ONLY>
-__device__ __forceinline__ uint32_t e4m3_encode_mag(float ay, uint32_t r16) {
+// case, decided once per wave).  ay must be non-negative; the element's random field is half HALF of `word`.
+template <int ROUND, bool NORMAL_ONLY, int HALF>
+__device__ __forceinline__ uint32_t e4m3_encode_mag(float ay, uint32_t word) {
   const uint32_t b = f2u(ay);
   uint32_t mag;
   if (ROUND == ROUND_SR) {
     uint32_t axis = b - (0x3C000000u - SR_CENTRE);          // code 8 <-> 0x3C800000
     if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = f2u(ay + 0x1p-6f) - (0x3C800000u - SR_CENTRE);
-    mag = (axis + (r16 << 4)) >> 20;                        // up iff frac20 + 16*r16 + 8 >= 2^20
+    mag = add_random_field<HALF>(axis, word) >> 20;         // up iff frac20 + 16*r16 + 8 >= 2^20
   } else {
     if (NORMAL_ONLY || b >= E4M3_MIN_NORMAL_BITS) {
       const uint32_t k = b - 0x3C000000u;
@@ -137,8 +151,8 @@ __device__ __forceinline__ float int4_decode_sixteenth(uint32_t packed, uint32_t
 // round(y) in [-7, 7] as a float carrying the sign of y (a zero result keeps y's sign: -0.0f decodes and
 // subtracts exactly like +0.0f everywhere it is used).  Needs |y| < 8 + 2^-3, which abs-max scaling guarantees
 // (|y| <= 7 (1 + 2^-8) even when a bf16 scale was rounded down).
-template <int ROUND>
-__device__ __forceinline__ float int4_round(float y, uint32_t r16) {
+template <int ROUND, int HALF>
+__device__ __forceinline__ float int4_round(float y, uint32_t word) {
   const float ay = __builtin_fabsf(y);
   uint32_t mag;
   if (ROUND == ROUND_SR) {
@@ -147,7 +161,7 @@ __device__ __forceinline__ float int4_round(float y, uint32_t r16) {
     // rounding rule, 8 units of 2^-20 -- an exact multiple of the ulp, so it commutes with the rounding -- which
     // leaves "up iff frac20 + 16*r16 + 8 >= 2^20" as one shift-and-add and a bit-field extract.  (|y| + 8 + 2^-17
     // can reach the next binade only for |y| > 7.9999, where bit 23 is set and the result saturates at 7 anyway.)
-    const uint32_t t = f2u(ay + (8.0f + 0x1p-17f)) + (r16 << 4);
+    const uint32_t t = add_random_field<HALF>(f2u(ay + (8.0f + 0x1p-17f)), word);
     mag = (t >> 20) & 15u;
   } else {
     mag = f2u(ay + 0x1p23f) - 0x4B000000u;                  // ulp(2^23) = 1: exact nearest-even

@@ -222,11 +222,11 @@ __device__ __forceinline__ void encode8(const float (&x)[8], float inv, const Ph
   const uint32_t rw[4] = {r.w0, r.w1, r.w2, r.w3};
   c[0] = 0; c[1] = 0;
   if (FMT == FMT_FP8) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-      c[j >> 2] |= e4m3_encode_mag<ROUND, NORMAL_ONLY>(__builtin_fabsf(x[j]) * inv, r16) << (8 * (j & 3));
-    }
+#define ECO_FP8_ELEM(J) \
+    c[J >> 2] |= e4m3_encode_mag<ROUND, NORMAL_ONLY, (J & 1)>(__builtin_fabsf(x[J]) * inv, rw[J >> 1]) << (8 * (J & 3));
+    ECO_FP8_ELEM(0) ECO_FP8_ELEM(1) ECO_FP8_ELEM(2) ECO_FP8_ELEM(3)
+    ECO_FP8_ELEM(4) ECO_FP8_ELEM(5) ECO_FP8_ELEM(6) ECO_FP8_ELEM(7)
+#undef ECO_FP8_ELEM
     // inv >= 0, so the sign of y is the sign of x
     c[0] |= sign_bytes4(x[0], x[1], x[2], x[3]);
     c[1] |= sign_bytes4(x[4], x[5], x[6], x[7]);
@@ -235,7 +235,7 @@ __device__ __forceinline__ void encode8(const float (&x)[8], float inv, const Ph
   } else {
     uint32_t even = 0, odd = 0;
 #define ECO_INT4_ELEM(J)                                                                              \
-    q[J] = int4_round<ROUND>(x[J] * inv, (J & 1) ? (rw[J >> 1] >> 16) : (rw[J >> 1] & 0xFFFFu));     \
+    q[J] = int4_round<ROUND, (J & 1)>(x[J] * inv, rw[J >> 1]);                                        \
     int4_insert<J>(q[J], even, odd);
     ECO_INT4_ELEM(0) ECO_INT4_ELEM(1) ECO_INT4_ELEM(2) ECO_INT4_ELEM(3)
     ECO_INT4_ELEM(4) ECO_INT4_ELEM(5) ECO_INT4_ELEM(6) ECO_INT4_ELEM(7)
@@ -255,7 +255,7 @@ __device__ __forceinline__ bool sqrt_plus_eps8(const float (&x)[8], float eps, f
     lo = lo < b ? lo : b;
     hi = hi > b ? hi : b;
   }
-  if (__all(lo >= SQRT_MID_LO && hi <= SQRT_MID_HI)) {
+  if (wave_all(lo >= SQRT_MID_LO && hi <= SQRT_MID_HI)) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) d[j] = sqrt_rn_midrange(x[j]) + eps;
     return true;
@@ -421,7 +421,7 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
   if (FMT == FMT_FP8) {
     // the E4M3 subnormal range (|y| < 2^-6) needs a second formula; it is rare, so decide per wave
     // (multiplication by inv >= 0 is monotone, so the smallest |y| is fl(min|theta~| * inv))
-    if (__any(absmin8(th) * inv < 0x1p-6f)) encode8<FMT, ROUND, false>(th, inv, r, cn, qn);
+    if (wave_any(absmin8(th) * inv < 0x1p-6f)) encode8<FMT, ROUND, false>(th, inv, r, cn, qn);
     else encode8<FMT, ROUND, true>(th, inv, r, cn, qn);
   } else {
     encode8<FMT, ROUND, true>(th, inv, r, cn, qn);
