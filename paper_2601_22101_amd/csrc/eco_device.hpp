@@ -48,17 +48,21 @@ __device__ __forceinline__ float e4m3_decode(uint32_t packed) {
   return __builtin_amdgcn_cvt_f32_fp8((int)packed, SEL);
 }
 
-// Correctly rounded fp32 square root for 2^-96 <= x <= 2^96: the hardware estimate (1 ulp) followed
-// by the two-sided residual test that picks the neighbour when the estimate is on the wrong side
-// of a rounding boundary.  It is the standard correctly-rounded sequence without the input scaling
-// and special-value handling that only matter outside that range; sqrtf() covers the rest.
+// Correctly rounded fp32 square root for 2^-96 <= x <= 2^96: the hardware's reciprocal-square-root estimate r (1 ulp),
+// g = x r and h = r / 2 as first approximations of sqrt(x) and 1 / (2 sqrt(x)), one coupled Newton step on the pair,
+// and a last correction of g by its exact residual x - g^2 (a fused multiply-add) times h.  It is the textbook
+// Newton-Markstein square root without the input scaling and special-value handling that only matter outside that
+// range; sqrtf() covers the rest.  (Compared on the device with sqrtf() for every fp32 of the range; the library's
+// self-test entry repeats the sweep.)
 __device__ __forceinline__ float sqrt_rn_midrange(float x) {
-  float y = __builtin_amdgcn_sqrtf(x);
-  const float ydn = u2f(f2u(y) - 1u), yup = u2f(f2u(y) + 1u);
-  const float rdn = fmaf(-ydn, y, x), rup = fmaf(-yup, y, x);
-  y = rdn <= 0.0f ? ydn : y;
-  y = rup > 0.0f ? yup : y;
-  return y;
+  const float r = __builtin_amdgcn_rsqf(x);
+  float g = x * r;
+  float h = 0.5f * r;
+  const float e = fmaf(-h, g, 0.5f);
+  g = fmaf(g, e, g);
+  h = fmaf(h, e, h);
+  const float d = fmaf(-g, g, x);
+  return fmaf(d, h, g);
 }
 constexpr uint32_t SQRT_MID_LO = 0x0F800000u;   // 2^-96
 constexpr uint32_t SQRT_MID_HI = 0x6F800000u;   // 2^96
@@ -96,42 +100,56 @@ constexpr float DIV_MID_N_LO = 0x1p-40f, DIV_MID_N_HI = 0x1p40f;      // numerat
 constexpr uint32_t E4M3_MIN_NORMAL_BITS = 0x3C800000u;     // fp32 bit pattern of 2^-6
 constexpr uint32_t SR_CENTRE = 8u;                         // half of the 2^4 fraction units one random unit is worth
 
-// f + 16 * h modulo 2^32, h = the low (HALF = 0) or high (HALF = 1) 16 bits of a Philox word: the random field of an
-// element, in units of 2^-20 of a grid step.  One v_mad_u32_u16 (u16 x u16 + u32; op_sel picks the half of the word).
-template <int HALF>
+// f + MUL * h modulo 2^32, h = the low (HALF = 0) or high (HALF = 1) 16 bits of a Philox word: the random field of an
+// element, 16 bits that stand for the top 16 of the 20 fraction bits of a grid step.  One v_mad_u32_u16 (u16 x u16 + u32;
+// op_sel picks the half of the word).
+template <int HALF, uint32_t MUL>
 __device__ __forceinline__ uint32_t add_random_field(uint32_t f, uint32_t word) {
   uint32_t t;
-  if (HALF) asm("v_mad_u32_u16 %0, %1, 16, %2 op_sel:[1,0,0,0]" : "=v"(t) : "v"(word), "v"(f));
-  else asm("v_mad_u32_u16 %0, %1, 16, %2" : "=v"(t) : "v"(word), "v"(f));
+  if constexpr (MUL <= 64u) {       // an inline constant
+    if (HALF) asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(t) : "v"(word), "n"(MUL), "v"(f));
+    else asm("v_mad_u32_u16 %0, %1, %2, %3" : "=v"(t) : "v"(word), "n"(MUL), "v"(f));
+  } else {                // from a scalar register
+    if (HALF) asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(t) : "v"(word), "s"(MUL), "v"(f));
+    else asm("v_mad_u32_u16 %0, %1, %2, %3" : "=v"(t) : "v"(word), "s"(MUL), "v"(f));
+  }
   return t;
 }
 
-// Magnitude code (0..126) of |y|.  NORMAL_ONLY: the caller guarantees |y| >= 2^-6 (the common
-// case, decided once per wave).  ay must be non-negative; the element's random field is half HALF of `word`.
+// The E4M3 code of y (magnitude ay >= 0, sign bit taken from `sign_from`) in the TOP BYTE of the returned word; the
+// lower bytes hold leftovers of the rounding arithmetic.  pack_top_bytes4() gathers four such words into a dword of
+// codes.  NORMAL_ONLY: the caller guarantees ay >= 2^-6 (the common case, decided once per wave).  The element's
+// random field is half HALF of `word`.
 template <int ROUND, bool NORMAL_ONLY, int HALF>
-__device__ __forceinline__ uint32_t e4m3_encode_mag(float ay, uint32_t word) {
+__device__ __forceinline__ uint32_t e4m3_encode_top(float ay, uint32_t word, uint32_t sign_from) {
   const uint32_t b = f2u(ay);
-  uint32_t mag;
+  uint32_t t;
   if (ROUND == ROUND_SR) {
-    uint32_t axis = b - (0x3C000000u - SR_CENTRE);          // code 8 <-> 0x3C800000
-    if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = f2u(ay + 0x1p-6f) - (0x3C800000u - SR_CENTRE);
-    mag = add_random_field<HALF>(axis, word) >> 20;         // up iff frac20 + 16*r16 + 8 >= 2^20
+    // position on the code axis in units of 2^-24 codes, (b - (0x3C000000 - 8)) << 4 (code 8 <-> 0x3C800000; below
+    // 2^28, so the arithmetic modulo 2^32 is exact): one shift-and-add; the random field then enters times 2^8 and
+    // the code is the top byte: up iff frac20 + 16 r + 8 >= 2^20
+    uint32_t axis = (b << 4) + (0u - ((0x3C000000u - SR_CENTRE) << 4));
+    if (!NORMAL_ONLY && b < E4M3_MIN_NORMAL_BITS) axis = (f2u(ay + 0x1p-6f) - (0x3C800000u - SR_CENTRE)) << 4;
+    t = add_random_field<HALF, 256u>(axis, word);
   } else {
+    uint32_t mag;
     if (NORMAL_ONLY || b >= E4M3_MIN_NORMAL_BITS) {
       const uint32_t k = b - 0x3C000000u;
       mag = (k + 0x7FFFFu + ((k >> 20) & 1u)) >> 20;        // nearest, ties to the even code
     } else {
       mag = f2u(ay + 0x1p14f) - 0x46800000u;                // ulp(2^14) = 2^-9: exact nearest-even
     }
+    t = mag << 24;
   }
-  return mag < 126u ? mag : 126u;                           // saturate at 448 (0x7E)
+  t = t < 0x7EFFFFFFu ? t : 0x7EFFFFFFu;                    // saturate at 448 (0x7E)
+  return t | (sign_from & 0x80000000u);
 }
 
-// Sign bits of four fp32 values as a dword of code sign bits: byte j = 0x80 if x_j is negative.
-__device__ __forceinline__ uint32_t sign_bytes4(float x0, float x1, float x2, float x3) {
-  const uint32_t lo = __builtin_amdgcn_perm(f2u(x1), f2u(x0), 0x0c0c0703u);   // bytes: x0.b3, x1.b3, 0, 0
-  const uint32_t hi = __builtin_amdgcn_perm(f2u(x3), f2u(x2), 0x07030c0cu);   // bytes: 0, 0, x2.b3, x3.b3
-  return (lo | hi) & 0x80808080u;
+// Byte j of the result = the top byte of t_j.
+__device__ __forceinline__ uint32_t pack_top_bytes4(uint32_t t0, uint32_t t1, uint32_t t2, uint32_t t3) {
+  const uint32_t lo = __builtin_amdgcn_perm(t1, t0, 0x0c0c0703u);   // bytes: t0.b3, t1.b3, 0, 0
+  const uint32_t hi = __builtin_amdgcn_perm(t3, t2, 0x07030c0cu);   // bytes: 0, 0, t2.b3, t3.b3
+  return lo | hi;
 }
 
 // ---------------------------------------------------------------------------------- INT4
@@ -161,7 +179,7 @@ __device__ __forceinline__ float int4_round(float y, uint32_t word) {
     // rounding rule, 8 units of 2^-20 -- an exact multiple of the ulp, so it commutes with the rounding -- which
     // leaves "up iff frac20 + 16*r16 + 8 >= 2^20" as one shift-and-add and a bit-field extract.  (|y| + 8 + 2^-17
     // can reach the next binade only for |y| > 7.9999, where bit 23 is set and the result saturates at 7 anyway.)
-    const uint32_t t = add_random_field<HALF>(f2u(ay + (8.0f + 0x1p-17f)), word);
+    const uint32_t t = add_random_field<HALF, 16u>(f2u(ay + (8.0f + 0x1p-17f)), word);
     mag = (t >> 20) & 15u;
   } else {
     mag = f2u(ay + 0x1p23f) - 0x4B000000u;                  // ulp(2^23) = 1: exact nearest-even

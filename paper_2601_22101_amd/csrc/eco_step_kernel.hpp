@@ -220,16 +220,16 @@ __device__ __forceinline__ float absmin8(const float (&x)[8]) {
 template <int FMT, int ROUND, bool NORMAL_ONLY>
 __device__ __forceinline__ void encode8(const float (&x)[8], float inv, const Philox4 &r, uint32_t (&c)[2], float (&q)[8]) {
   const uint32_t rw[4] = {r.w0, r.w1, r.w2, r.w3};
-  c[0] = 0; c[1] = 0;
+  c[1] = 0;
   if (FMT == FMT_FP8) {
-#define ECO_FP8_ELEM(J) \
-    c[J >> 2] |= e4m3_encode_mag<ROUND, NORMAL_ONLY, (J & 1)>(__builtin_fabsf(x[J]) * inv, rw[J >> 1]) << (8 * (J & 3));
+    // inv >= 0, so the sign of y is the sign of x
+    uint32_t t[8];
+#define ECO_FP8_ELEM(J) t[J] = e4m3_encode_top<ROUND, NORMAL_ONLY, (J & 1)>(__builtin_fabsf(x[J]) * inv, rw[J >> 1], f2u(x[J]));
     ECO_FP8_ELEM(0) ECO_FP8_ELEM(1) ECO_FP8_ELEM(2) ECO_FP8_ELEM(3)
     ECO_FP8_ELEM(4) ECO_FP8_ELEM(5) ECO_FP8_ELEM(6) ECO_FP8_ELEM(7)
 #undef ECO_FP8_ELEM
-    // inv >= 0, so the sign of y is the sign of x
-    c[0] |= sign_bytes4(x[0], x[1], x[2], x[3]);
-    c[1] |= sign_bytes4(x[4], x[5], x[6], x[7]);
+    c[0] = pack_top_bytes4(t[0], t[1], t[2], t[3]);
+    c[1] = pack_top_bytes4(t[4], t[5], t[6], t[7]);
     q[0] = e4m3_decode<0>(c[0]); q[1] = e4m3_decode<1>(c[0]); q[2] = e4m3_decode<2>(c[0]); q[3] = e4m3_decode<3>(c[0]);
     q[4] = e4m3_decode<0>(c[1]); q[5] = e4m3_decode<1>(c[1]); q[6] = e4m3_decode<2>(c[1]); q[7] = e4m3_decode<3>(c[1]);
   } else {
