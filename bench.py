@@ -397,7 +397,7 @@ def main() -> int:
                          "gaps, m first and v last with codes, scales and gradients between them (dense) or in the order codes, "
                          "scales, gradients, m, v (dense-default); one allocation without gaps, m first and v after as many of "
                          "the other arenas as the library's bandwidth probe finds fastest at set-up (probed; auto = probed for "
-                         "FP8 / fp32-state workloads of 8 GiB and more, dense for other large ones); one allocation with the "
+                         "FP8 / fp32-state Adam workloads of 8 GiB and more, dense for other large ones); one allocation with the "
                          "codes+gradient, m and v arenas tens of GiB of unused memory apart (spread)")
     ap.add_argument("--spread-gap-gib", type=int, default=0, help="distance between the arena groups of the spread placement (0 = default)")
     ap.add_argument("--calibrate-gaps", type=int, default=3,
@@ -406,9 +406,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true", help="skip the untimed parity step after the timed region")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the copy-kernel ceilings after the timed region")
-    ap.add_argument("--compare-placements", default="dense,packed,spread",
-                    help="comma-separated placements to time the same step on after the headline run (configuration 4, "
-                         "headline variant only; empty = none)")
+    ap.add_argument("--compare-placements", default=None,
+                    help="comma-separated placements to time the same step on after the main run (configuration 4 only; "
+                         "default: dense,packed,spread for the headline variant, none for the others; empty = none)")
     ap.add_argument("--bulk-grad", action="store_true",
                     help="draw each step's gradients with a few generator calls over the whole arena instead of one "
                          "per tensor (same distribution; for runs under rocprofv3 --pmc)")
@@ -549,10 +549,13 @@ def main() -> int:
     dw.close()
     del dw
     torch.cuda.empty_cache()
-    others = [p for p in args.compare_placements.split(",") if p] if headline and args.config == 4 else []
+    if args.compare_placements is None:
+        args.compare_placements = "dense,packed,spread" if headline else ""
+    others = [p for p in args.compare_placements.split(",") if p] if args.config == 4 else []
     for other in others:
-        dw2 = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk", placement=other, grad_sets=min(grad_sets, 4),
-                                     calibrate_gaps=0)
+        bulk_ok = over.get("mode", eco.ECO_MODE_ECO) in (eco.ECO_MODE_ECO, eco.ECO_MODE_NAIVE)
+        dw2 = harness.DeviceWorkload(wl, "cuda:0", layout=over, init="bulk" if bulk_ok else True, placement=other,
+                                     grad_sets=min(grad_sets, 4), calibrate_gaps=0)
         if dw2.placement == placement_used:
             dw2.close()
             continue

@@ -64,7 +64,7 @@ class DeviceWorkload:
         In the master-weight mode the fp32 initial weights are kept as the master copy; in the
         exact-injection mode the aux buffer starts as e_0 = theta_0 - q(theta_0) (Appendix A).
         `placement`: "packed", "dense", "probed" or "spread" (see the class comment); "auto" = probed for large
-        workloads the probe's byte mix fits (FP8 codes, block-wise fp32 scales, fp32 state, Adam), dense for other
+        workloads the probe's arrays fit (FP8 codes, fp32 state, Adam, with or without master weights), dense for other
         large ones, packed for small ones.  `skew_bytes` / `single_allocation` place arenas by hand (probes).
         `order`: "default" lays the arenas out as codes, scales, gradients, m, v; "state-apart" (one allocation only)
         puts m first and v last with everything else between them, no byte unused.
@@ -218,28 +218,35 @@ class DeviceWorkload:
         self.plan = self.plans[0]
 
     def _probe_fits(self) -> bool:
-        """The library's bandwidth probe moves the bytes of the FP8 / fp32-state Adam step with block-128 fp32 scales;
-        it is run on a workload's own arenas only where those are at least as large as what it touches."""
+        """The library's bandwidth probe moves the bytes of the FP8 / fp32-state Adam step; it is run on a workload's own
+        arenas where those are at least as large as what it touches: FP8 codes (any scale granularity), fp32 state,
+        Adam, with or without master weights."""
         wl = self.wl
         quant = [t for t in wl.tensors if t.fmt in ("fp8", "int4")]
-        return (not wl.state_bf16 and not wl.scale_bf16 and wl.block_size == 128 and len(quant) > 0 and
-                all(t.fmt == "fp8" and t.group_size(128) == 128 for t in quant) and
-                self.mode in (eco.ECO_MODE_ECO, eco.ECO_MODE_NAIVE) and self.layout.get("opt", eco.ECO_OPT_ADAM) == eco.ECO_OPT_ADAM)
+        return (not wl.state_bf16 and len(quant) > 0 and all(t.fmt == "fp8" for t in quant) and
+                self.layout.get("opt", eco.ECO_OPT_ADAM) == eco.ECO_OPT_ADAM)
 
     def _probe_orders(self, pool_buf, pool_pos, off, soff, code_bytes, woff, grad_sets):
         """Candidate orders of the arenas, none of which leaves a byte unused: m first and v after the first k of the
-        other arenas (codes + scales + unquantized weights as one unit, then the gradient arenas), k = 1 .. all of
-        them; and, mirrored, v last and m before the last k.  The probe is timed on each candidate's addresses in the
+        other arenas (codes + scales + unquantized weights as one unit, then the gradient arenas, then the master
+        weights if the mode keeps them), k = 1 .. all of them; and, mirrored, v last and m before the last k.  The probe is timed on each candidate's addresses in the
         still uninitialised allocation.  Returns the fastest order with its figures (None if the workload is too small
         to probe); "contrast" = fastest / slowest candidate."""
-        sizes = {"codes": max(code_bytes, 1), "scales": 4 * max(soff, 1), "plain": 2 * max(woff, 1), "m": 4 * off, "v": 4 * off}
+        scale_bytes = (2 if self.wl.scale_bf16 else 4) * max(soff, 1)
+        sizes = {"codes": max(code_bytes, 1), "scales": scale_bytes, "plain": 2 * max(woff, 1), "m": 4 * off, "v": 4 * off}
         grads = ["grad"] + [f"grad_extra{k}" for k in range(1, grad_sets)]
         for g in grads:
             sizes[g] = 2 * off
         fillers = [["codes", "scales", "plain"]] + [[g] for g in grads]
+        if self.mode in (eco.ECO_MODE_EXACT, eco.ECO_MODE_MASTER):
+            sizes["aux"] = 4 * off
+            fillers.append(["aux"])
         numel = min(code_bytes, off) // 1024 * 1024
         if numel == 0:
             return None
+        # the probe reads and rewrites one fp32 scale per 128 elements; where the workload's own scale array is smaller
+        # (bf16 scales, one scale per row or per tensor) the start of the code array stands in for it
+        probe_scales = "scales" if scale_bytes >= numel // 128 * 4 else "codes"
         F = len(fillers)
         flat = lambda units: [n for u in units for n in u]
         orders = [["m"] + flat(fillers[:k]) + ["v"] + flat(fillers[k:]) for k in range(1, F + 1)]
@@ -255,7 +262,7 @@ class DeviceWorkload:
             assert pos <= pool_buf.numel()
             a = {n: base + at[n] for n in ("codes", "scales", "grad", "m", "v")}
             for i in range(3):                      # one warm-up launch, two timed ones
-                eco.eco_bandwidth_probe(0, a["codes"], a["scales"], a["grad"], a["m"], a["v"], numel)
+                eco.eco_bandwidth_probe(0, a["codes"], a[probe_scales], a["grad"], a["m"], a["v"], numel)
                 ev[i].record()
             torch.cuda.synchronize(self.device)
             results.append((min(ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])), idx, at))
@@ -263,7 +270,7 @@ class DeviceWorkload:
         gib = lambda x: round((x - pool_pos) / 2**30, 1)
         figures = [{"gib_into_the_allocation": {n: gib(at_[n]) for n in ("m", "v", "codes", "grad")},
                     "probe_gbs": round(numel * 20.0625 / ms / 1e6)} for ms, _, at_ in results]
-        units = ["m" if n == "m" else "v" if n == "v" else "codes, scales" if n == "codes" else "g" for n in orders[best]
+        units = [{"m": "m", "v": "v", "codes": "codes, scales", "aux": "master weights"}.get(n, "g") for n in orders[best]
                  if n not in ("scales", "plain")]
         runs = []                                                # "g g g" -> "3 gradient arenas"
         for u in units:
