@@ -145,7 +145,7 @@ int default_waves(const eco::KernelVariant &kv) {
 }
 
 // The cap is expressed as a dynamic-LDS request the kernels never touch (160 KB of LDS per compute unit).
-// For Adam the wide-group kernel measured best at the same cap, the two tensor-wise passes with three waves more.
+// For Adam the wide-group kernel measured best at the same cap, the two tensor-wise passes with four waves more.
 uint32_t lds_for_waves(int waves, int granule) {
   return waves > 0 ? static_cast<uint32_t>(163840 / waves / granule * granule) : 0u;
 }
@@ -228,7 +228,7 @@ void fill_step_scalars(const eco_hparams_t *hp, const eco_constants_t &c, const 
   const int64_t opt_lds_wave = g_lds_bytes_wave.load(std::memory_order_relaxed);
   a->lds_bytes = opt_lds >= 0 ? static_cast<uint32_t>(opt_lds) : lds_for_waves(waves, 512);
   a->lds_bytes_wave = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide, 256);
-  a->lds_bytes_tw = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide ? waves_wide + 3 : 0, 256);
+  a->lds_bytes_tw = opt_lds_wave >= 0 ? static_cast<uint32_t>(opt_lds_wave) : lds_for_waves(waves_wide ? waves_wide + 4 : 0, 256);
 }
 
 
