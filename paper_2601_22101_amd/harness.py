@@ -190,7 +190,10 @@ class DeviceWorkload:
             losers, tried = [], 1
             while (best is not None and best["contrast"] < 1.07 and tried < 3 and
                    torch.cuda.mem_get_info(dev)[0] >= need + (8 << 30)):
-                other_buf = torch.zeros(need, dtype=torch.uint8, device=dev)
+                try:
+                    other_buf = torch.zeros(need, dtype=torch.uint8, device=dev)
+                except torch.cuda.OutOfMemoryError:
+                    break
                 other_pos = (-other_buf.data_ptr()) % (1 << 21)
                 other = self._probe_orders(other_buf, other_pos, off, soff, code_bytes, woff, grad_sets)
                 tried += 1
