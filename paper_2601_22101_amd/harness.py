@@ -230,6 +230,18 @@ class DeviceWorkload:
         return (not wl.state_bf16 and len(quant) > 0 and all(t.fmt == "fp8" for t in quant) and
                 self.layout.get("opt", eco.ECO_OPT_ADAM) == eco.ECO_OPT_ADAM)
 
+    @staticmethod
+    def candidate_orders(fillers: List[List[str]]) -> List[List[str]]:
+        """Orders of the arenas the placement probe times.  `fillers`: the arenas other than m and v as units that stay
+        together (codes + scales + unquantized weights; each gradient arena; the master weights), in their usual
+        order.  m first and v after the first k units, k = 1 .. all; and, mirrored, v last and m before the last k,
+        k = 1 .. all but one (k = all is the first family's last order again)."""
+        F = len(fillers)
+        flat = lambda units: [n for u in units for n in u]
+        orders = [["m"] + flat(fillers[:k]) + ["v"] + flat(fillers[k:]) for k in range(1, F + 1)]
+        orders += [flat(fillers[:F - k]) + ["m"] + flat(fillers[F - k:]) + ["v"] for k in range(1, F)]
+        return orders
+
     def _probe_orders(self, pool_buf, pool_pos, off, soff, code_bytes, woff, grad_sets):
         """Candidate orders of the arenas, none of which leaves a byte unused: m first and v after the first k of the
         other arenas (codes + scales + unquantized weights as one unit, then the gradient arenas, then the master
@@ -251,10 +263,7 @@ class DeviceWorkload:
         # the probe reads and rewrites one fp32 scale per 128 elements; where the workload's own scale array is smaller
         # (bf16 scales, one scale per row or per tensor) the start of the code array stands in for it
         probe_scales = "scales" if scale_bytes >= numel // 128 * 4 else "codes"
-        F = len(fillers)
-        flat = lambda units: [n for u in units for n in u]
-        orders = [["m"] + flat(fillers[:k]) + ["v"] + flat(fillers[k:]) for k in range(1, F + 1)]
-        orders += [flat(fillers[:F - k]) + ["m"] + flat(fillers[F - k:]) + ["v"] for k in range(1, F)]
+        orders = self.candidate_orders(fillers)
         base = pool_buf.data_ptr()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         results = []

@@ -245,6 +245,33 @@ def test_harness_arena_layout_is_aligned_and_fits_its_pool(eco):
             assert D.pool_bytes(wl, mode, sets) >= need
 
 
+def test_harness_candidate_orders_use_every_arena_once():
+    """Host logic of the probed placement: every candidate order is a permutation of the same arenas (so none leaves a
+    byte unused or an arena out), units stay together and in their order, the candidates are distinct, and between
+    them v follows m at every possible distance."""
+    from paper_2601_22101_amd.harness import DeviceWorkload as D
+    for fillers in ([["codes", "scales", "plain"], ["grad"]],
+                    [["codes", "scales", "plain"]] + [[f"g{k}"] for k in range(8)],
+                    [["codes", "scales", "plain"], ["grad"], ["grad_extra1"], ["aux"]]):
+        names = sorted(["m", "v"] + [n for u in fillers for n in u])
+        orders = D.candidate_orders(fillers)
+        F = len(fillers)
+        assert len(orders) == 2 * F - 1 and len({tuple(o) for o in orders}) == len(orders)
+        gaps = set()
+        for o in orders:
+            assert sorted(o) == names
+            assert o.index("m") < o.index("v")
+            rest = [n for n in o if n not in ("m", "v")]
+            assert rest == [n for u in fillers for n in u]                 # the other arenas keep their order
+            for u in fillers:                                              # and a unit is never split by m or v
+                i = o.index(u[0])
+                assert o[i:i + len(u)] == u
+            assert o[0] == "m" or o[-1] == "v"
+            gaps.add((o[0] == "m", sum(1 for u in fillers if o.index("m") < o.index(u[0]) < o.index("v"))))
+        assert {g for first, g in gaps if first} == set(range(1, F + 1))
+        assert {g for first, g in gaps if not first} == set(range(1, F))
+
+
 def test_a_plain_c_client_compiles_links_and_runs(eco, tmp_path):
     """include/eco.h is valid C99 (-Wall -Wextra -pedantic -Werror), libeco.so links by its C names, and the
     host-only entry points give a C caller what they give the Python binding."""
