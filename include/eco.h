@@ -174,7 +174,8 @@ eco_status_t eco_plan_destroy(eco_plan_t *plan);
  * Asynchronous on `stream`; allocates nothing.  Launches per storage format present: one kernel over the full
  * 512-element tiles of block-scaled tensors, one over their ragged tails if any, one per workgroup size for wide
  * groups, and four for tensors with a single scale (abs-max pass into the plan's scratch, its reduction, apply
- * pass, scale write).  Steps of one plan that use that scratch must not overlap each other on different streams.
+ * pass, scale write); a plan with more work than one launch can hold (2^32 threads: about 2^35 elements) has these
+ * launched in pieces.  Steps of one plan that use that scratch must not overlap each other on different streams.
  * hp->block_size, state_dtype, scale_dtype, opt and mode must equal the plan's, and the device that was current at
  * eco_plan_create must be current (ECO_EINVAL otherwise).
  */
