@@ -240,8 +240,11 @@ def parity_step(dw, wl, step: int, gset: int, n_tensors: int = 40) -> dict:
         gs = tv.spec.group_size(wl.block_size)
         e0, e1 = g0 * gs, min((g0 + n) * gs, tv.spec.numel)
         codes = tv.weights[e0:e1] if tv.spec.fmt == "fp8" else tv.weights[e0 // 2:(e1 + 1) // 2]
-        return dict(codes=codes.cpu().numpy().copy(), scales=f32(tv.scales[g0:g0 + n]), grad=bits16(dw.grad_view(tv, gset)[e0:e1]),
-                    m=f32(tv.m[e0:e1]), v=f32(tv.v[e0:e1])), e1 - e0
+        h = dict(codes=codes.cpu().numpy().copy(), scales=f32(tv.scales[g0:g0 + n]), grad=bits16(dw.grad_view(tv, gset)[e0:e1]),
+                 m=f32(tv.m[e0:e1]), v=f32(tv.v[e0:e1]))
+        if tv.aux is not None:                       # master weights, or the stored error of the exact injection
+            h["aux"] = f32(tv.aux[e0:e1])
+        return h, e1 - e0
 
     before = [grab(*sp) for sp in spans]
     hp = dw.hparams(step)
@@ -256,12 +259,15 @@ def parity_step(dw, wl, step: int, gset: int, n_tensors: int = 40) -> dict:
                                 state_bf16=wl.state_bf16, scale_bf16=wl.scale_bf16, lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2,
                                 eps=hp.eps, weight_decay=hp.weight_decay, step=hp.step, seed=hp.seed, elem_offset=g0 * gs,
                                 tensor_id=i)
-        assert o.eco_step(cfg, numel, h["m"], h["v"], codes=h["codes"], scales=h["scales"], grad_bf16=h["grad"]) == 0
+        assert o.eco_step(cfg, numel, h["m"], h["v"] if hp.opt == 0 else None, codes=h["codes"], scales=h["scales"],
+                          grad_bf16=h["grad"], aux=h.get("aux")) == 0
         got, _ = grab(i, g0, n)
+        if "aux" in h:
+            out["aux_bit_mismatches"] = out.get("aux_bit_mismatches", 0) + int((got["aux"].view(np.uint32) != h["aux"].view(np.uint32)).sum())
         out["elements"] += numel
         out["code_mismatches"] += int((got["codes"] != h["codes"]).sum())
         out["scale_mismatches"] += int((got["scales"].view(np.uint32) != h["scales"].view(np.uint32)).sum())
-        for key in ("m", "v"):
+        for key in ("m", "v") if hp.opt == 0 else ("m",):
             a, b = got[key].astype(np.float64), h[key].astype(np.float64)
             rel = np.abs(a - b) / np.maximum(np.abs(b), 1e-30)
             out[f"{key}_max_rel"] = max(out[f"{key}_max_rel"], float(rel.max()))
@@ -531,7 +537,7 @@ def main() -> int:
                      "kernel_ms_median": sorted(kernel_ms)[len(kernel_ms) // 2], "kernel_ms_min": min(kernel_ms)},
     }
     quantized_only = all(t.fmt in ("fp8", "int4") for t in wl.tensors)
-    if not args.no_parity and not args.no_cpu_baseline and "master" not in args.variant and "exact" not in args.variant:
+    if not args.no_parity and not args.no_cpu_baseline:
         out["parity"] = parity_step(dw, wl, k + 1, k % grad_sets)
         print(f"[bench] parity: {out['parity']}", file=sys.stderr, flush=True)
     if not args.no_ceiling and args.config in (3, 4) and quantized_only and args.granularity == "block":
