@@ -61,6 +61,47 @@ def test_short_square_root_and_division_are_correctly_rounded(eco):
             eco.eco_arith_selftest(*args, bad)
 
 
+def test_bandwidth_probe_touches_what_it_says_and_nothing_else(eco):
+    """The measurement aid moves real bytes: the plain copy copies m to v; the byte-mix copy swaps m and v, mixes the
+    gradient into the codes, rewrites the scales with their own values and leaves the gradient alone; neither writes
+    a byte beyond the `numel` elements it was given (guard regions before and after every array)."""
+    n, guard = 8 * 1024, 1024
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+
+    def arr(count, dtype):
+        if dtype.is_floating_point:         # finite values: the probe passes m through one floating-point addition of zero
+            full = torch.randn(count + 2 * guard, dtype=dtype, device=DEV, generator=gen) + 3.0
+        else:
+            full = torch.randint(0, 255, ((count + 2 * guard) * torch.empty(0, dtype=dtype).element_size(),), dtype=torch.uint8,
+                                 device=DEV, generator=gen).view(dtype)
+        return full, full[guard:guard + count]
+    codes_f, codes = arr(n, torch.uint8)
+    scales_f, scales = arr(n // 128, torch.float32)
+    grad_f, grad = arr(n, torch.int16)
+    m_f, m = arr(n, torch.float32)
+    v_f, v = arr(n, torch.float32)
+    m_f, v_f, m, v = m_f.view(torch.int32), v_f.view(torch.int32), m.view(torch.int32), v.view(torch.int32)
+    before = {k: t.clone() for k, t in dict(codes=codes_f, scales=scales_f.view(torch.int32), grad=grad_f, m=m_f, v=v_f).items()}
+    eco.eco_bandwidth_probe(1, None, None, None, m, v, n)
+    torch.cuda.synchronize()
+    assert torch.equal(v, m) and torch.equal(m_f, before["m"])
+    assert torch.equal(v_f[:guard], before["v"][:guard]) and torch.equal(v_f[guard + n:], before["v"][guard + n:])
+    assert torch.equal(codes_f, before["codes"]) and torch.equal(grad_f, before["grad"])
+    v_f.copy_(before["v"])
+    eco.eco_bandwidth_probe(0, codes, scales, grad, m, v, n)
+    torch.cuda.synchronize()
+    b = {k: t[guard:guard + c] for (k, t), c in zip(before.items(), (n, n // 128, n, n, n))}
+    assert torch.equal(m, b["v"]) and torch.equal(v, b["m"]), "m and v swap"
+    assert torch.equal(scales.view(torch.int32), b["scales"]) and torch.equal(grad, b["grad"])
+    g = b["grad"].view(torch.int32).view(-1, 4)                     # a lane's 8 gradients: four dwords
+    want = b["codes"].view(torch.int32).view(-1, 2) ^ torch.stack([g[:, 0] ^ g[:, 2], g[:, 1] ^ g[:, 3]], dim=1)
+    assert torch.equal(codes.view(torch.int32).view(-1, 2), want)
+    for name, full, count in (("codes", codes_f, n), ("scales", scales_f.view(torch.int32), n // 128), ("grad", grad_f, n),
+                              ("m", m_f, n), ("v", v_f, n)):
+        assert torch.equal(full[:guard], before[name][:guard]) and torch.equal(full[guard + count:], before[name][guard + count:]), name
+
+
 def test_decode_every_code(eco, o32):
     codes = torch.arange(256, dtype=torch.uint8, device=DEV)
     scales = torch.ones(2, dtype=torch.float32, device=DEV)
