@@ -102,6 +102,70 @@ def test_bandwidth_probe_touches_what_it_says_and_nothing_else(eco):
         assert torch.equal(full[:guard], before[name][:guard]) and torch.equal(full[guard + count:], before[name][guard + count:]), name
 
 
+@pytest.mark.parametrize("fmt", [0, 1])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_no_entry_point_writes_outside_its_arrays(eco, fmt, bf16):
+    """Every array of every tensor sits between two guard regions of random bytes, with no padding after its last element:
+    the initial quantizer, the step (block-scaled tensors with ragged tails, rows that do not fill their workgroup, a
+    ragged last row, one scale per tensor; through a plan, plan-less and allocation-free), the de-quantizer and the
+    error call must leave every guard byte as it was -- and the read-only gradient too."""
+    guard = 4096
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(17 + fmt + 2 * bf16)
+    sdt = torch.bfloat16 if bf16 else torch.float32
+    dt = eco.ECO_DT_BF16 if bf16 else eco.ECO_DT_FP32
+    held = []
+
+    def arr(nbytes):
+        """nbytes of payload between two guards; returns the payload as a uint8 view (16-byte aligned start)."""
+        full = torch.randint(0, 256, (guard + nbytes + guard,), dtype=torch.uint8, device=DEV, generator=gen)
+        held.append((full, full.clone(), nbytes))
+        return full[guard:guard + nbytes]
+
+    cases = [(1, 128), (7, 128), (127, 32), (513, 128), (4097, 64), (12345, 512), (5 * 1000, 1000), (3 * 520, 520),
+             (2 * 1000 + 40, 1000), (2 * 8192 + 8, 8192), (100, 1 << 20), (70001, 1 << 20), (8193, 8193)]
+    tensors, payload = [], []
+    for tid, (numel, gs) in enumerate(cases):
+        if fmt == 1 and numel % 2:
+            numel += 1                                   # INT4 packs two codes a byte; an odd tail shares its byte
+            if gs >= numel - 1:
+                gs = max(gs, numel)                      # ... and one scale for the tensor stays one scale
+        ngroups = (numel + gs - 1) // gs
+        codes = arr(numel if fmt == 0 else numel // 2)
+        scales = arr(ngroups * (2 if bf16 else 4)).view(sdt)
+        grad = arr(2 * numel).view(torch.bfloat16)
+        m = arr(numel * (2 if bf16 else 4)).view(sdt)
+        v = arr(numel * (2 if bf16 else 4)).view(sdt)
+        src = arr(4 * numel).view(torch.float32)
+        out = arr(4 * numel).view(torch.float32)
+        src.copy_(torch.randn(numel, device=DEV, generator=gen) * 0.02)
+        grad.copy_((torch.randn(numel, device=DEV, generator=gen) * 1e-3).to(torch.bfloat16))
+        m.copy_((torch.randn(numel, device=DEV, generator=gen) * 1e-3).to(sdt))
+        v.copy_((torch.rand(numel, device=DEV, generator=gen) * 1e-6).to(sdt))
+        eco.eco_quantize_init(src, eco.ECO_DT_FP32, numel, fmt, gs, dt, codes, scales)
+        tensors.append(eco.make_tensor(codes, scales, grad, m, v, numel, tid, fmt, group_size=gs))
+        payload.append((numel, gs, codes, scales, grad, m, v, src, out))
+    torch.cuda.synchronize()
+    for full, ref, nbytes in held:                       # set-up is done: from here on the guards must not move
+        ref.copy_(full)
+    grads = [p[4].clone() for p in payload]
+    hp = lambda k: eco.make_hparams(block_size=128, state_dtype=dt, scale_dtype=dt, lr=1e-3, step=k, seed=9)
+    with eco.Plan(tensors, hp(1)) as plan:
+        plan.step(hp(1))
+    eco.eco_step_tensors(tensors, hp(2))
+    eco.eco_step_tensors_noalloc(tensors, hp(3))
+    for numel, gs, codes, scales, grad, m, v, src, out in payload:
+        eco.eco_dequantize(codes, scales, numel, fmt, gs, dt, out)
+        eco.eco_quantize_error(src, eco.ECO_DT_FP32, codes, scales, numel, fmt, gs, dt, out)
+    torch.cuda.synchronize()
+    for full, ref, nbytes in held:
+        assert torch.equal(full[:guard], ref[:guard]), "bytes before an array were written"
+        assert torch.equal(full[guard + nbytes:], ref[guard + nbytes:]), "bytes after an array were written"
+    for (numel, gs, codes, scales, grad, m, v, src, out), g0 in zip(payload, grads):
+        assert torch.equal(grad.view(torch.int16), g0.view(torch.int16)), "the gradient is read-only"
+        assert bool(torch.isfinite(m.float()).all()) and bool(torch.isfinite(out).all())
+
+
 def test_decode_every_code(eco, o32):
     codes = torch.arange(256, dtype=torch.uint8, device=DEV)
     scales = torch.ones(2, dtype=torch.float32, device=DEV)
