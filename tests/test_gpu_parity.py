@@ -506,6 +506,41 @@ def _equal(a, b):
     return all(all((x is None and y is None) or torch.equal(x, y) for x, y in zip(ta, tb)) for ta, tb in zip(a, b))
 
 
+def test_plans_of_their_own_may_step_concurrently_on_two_streams(harness, eco):
+    """eco_step keeps no state outside its plan: two plans (each with block-scaled, row-wise and tensor-wise tensors, so
+    each with abs-max scratch of its own) stepped at the same time on two streams give what they give one after the
+    other.  Larger tensors than elsewhere in this file, so that the launches of the two streams do overlap."""
+    T = workloads.TensorSpec
+    def wl(name, fmt):
+        ts = [T("blocks", (512, 2048), fmt), T("ragged", (300001,), fmt), T("rows", (300, 2048), fmt, granularity="row"),
+              T("whole", (5 * 65536 + 7 * 8,), fmt, granularity="tensor"), T("whole_small", (4096,), fmt, granularity="tensor"),
+              T("norm", (2048,), "bf16_plain")]
+        return workloads.Workload(name, ts, steps=3)
+    results = {}
+    for mode in ("serial", "concurrent"):
+        a = harness.DeviceWorkload(wl("two_streams_a", "fp8"), DEV)
+        b = harness.DeviceWorkload(wl("two_streams_b", "int4"), DEV)
+        for k in (1, 2, 3):
+            a.fill_gradients(k)
+            b.fill_gradients(k)
+            torch.cuda.synchronize()
+            if mode == "serial":
+                a.step(k)
+                torch.cuda.synchronize()
+                b.step(k)
+            else:
+                s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+                with torch.cuda.stream(s1):
+                    a.step(k)
+                with torch.cuda.stream(s2):
+                    b.step(k)
+            torch.cuda.synchronize()
+        results[mode] = (_snapshot(a), _snapshot(b))
+        a.close()
+        b.close()
+    assert _equal(results["serial"][0], results["concurrent"][0]) and _equal(results["serial"][1], results["concurrent"][1])
+
+
 def test_results_do_not_depend_on_launch_geometry_or_plan_order(harness, eco):
     wl = small_mixed_workload("fp8")
     results = []
