@@ -361,6 +361,23 @@ def _run_with_layout(harness, o32, wl, steps, over):
 
 
 @pytest.mark.parametrize("fmt", ["fp8", "int4"])
+@pytest.mark.parametrize("grad_std,over", [(1e-17, {}), (1e-20, {}), (1e18, {}), (1e-3, dict(lr=1e-14)), (1e-3, dict(lr=1e-3, eps=2.0)),
+                                           (1e-3, dict(lr=50.0, beta1=0.5)), (1e-3, dict(eps=0.0, beta2=0.0))])
+def test_operands_outside_the_short_forms_take_the_long_ones(harness, o32, fmt, grad_std, over):
+    """The kernels use short square-root and division sequences inside operand ranges and sqrtf / `/` outside them; here
+    the operands are outside: second moments below 2^-96 (gradients of 1e-17), denormal ones (1e-20), above 2^96 (1e18), a
+    numerator eta / (1 - beta1^k) below 2^-40, epsilon above 1, a huge learning rate, and beta2 = epsilon = 0.  Every code,
+    scale and state value must still be the oracle's."""
+    T = workloads.TensorSpec
+    ts = [T("a", (8, 1024), fmt, grad_std=grad_std), T("ragged", (4097,), fmt, grad_std=grad_std),
+          T("rows", (6, 1000), fmt, grad_std=grad_std, granularity="row"), T("whole", (20000,), fmt, grad_std=grad_std, granularity="tensor"),
+          T("mixed", (4096,), fmt, grad_std=1e-3), T("norm", (600,), "bf16_plain", grad_std=grad_std)]
+    wl = workloads.Workload("extremes_" + fmt, ts, steps=3)
+    worst = _run_with_layout(harness, o32, wl, 3, dict(over))
+    assert worst["code_mismatch"] == 0 and worst["m_bit_mismatch"] == 0 and worst["v_bit_mismatch"] == 0, worst
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
 @pytest.mark.parametrize("opt,mode,rnd", [(0, 3, 0), (0, 3, 1), (1, 3, 0), (1, 2, 0), (1, 2, 1)])
 def test_master_weight_and_exact_injection_modes(harness, o32, fmt, opt, mode, rnd):
     """ECO_MODE_MASTER (fp32 master copy, Sec. 3.1) and ECO_MODE_EXACT (stored error, Appendix A) on ragged tensors."""
