@@ -41,6 +41,34 @@ def test_philox_stream_is_bit_exact(eco, o32):
         assert np.array_equal(got, o32.philox_fill(seed, step, tid, n, first_word=first)), (seed, step, tid, first)
 
 
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_the_step_uses_every_bit_of_seed_step_and_tensor_id(eco, o32, fmt):
+    """The largest values the counter words take: seed 2^64 - 1 and other 64-bit seeds, tensor_id 2^32 - 1, steps beyond
+    2^31 and 2^32 (only the low word enters the counter; the bias corrections have long since reached 1).  The step's own
+    random stream must be the oracle's for all of them."""
+    from types import SimpleNamespace
+    n = 3 * 512 + 200
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(3)
+    src = torch.randn(n, device=DEV, generator=gen) * 0.02
+    for seed, step, tid in ((2 ** 64 - 1, 1, 2 ** 32 - 1), (0x8000000000000001, 2 ** 31 + 5, 0x80000000),
+                            (0xFEDCBA9876543210, 2 ** 32 + 3, 0xFFFF0000), (0, 2 ** 40 + 1, 1)):
+        codes = torch.zeros(n if fmt == 0 else n // 2, dtype=torch.uint8, device=DEV)
+        scales = torch.zeros((n + 127) // 128, dtype=torch.float32, device=DEV)
+        eco.eco_quantize_init(src, eco.ECO_DT_FP32, n, fmt, 128, eco.ECO_DT_FP32, codes, scales)
+        grad = (torch.randn(n, device=DEV, generator=gen) * 1e-3).to(torch.bfloat16)
+        m = torch.randn(n, device=DEV, generator=gen) * 1e-3
+        v = torch.rand(n, device=DEV, generator=gen) * 1e-6
+        tv = SimpleNamespace(weights=codes, scales=scales, grad=grad, m=m, v=v, aux=None)
+        h = host_copy(tv)
+        hp = eco.make_hparams(lr=1e-3, step=step, seed=seed)
+        eco.eco_step_tensors([eco.make_tensor(codes, scales, grad, m, v, n, tid, fmt)], hp)
+        torch.cuda.synchronize()
+        oracle_step(o32, h, n, step_config(hp, tid, fmt))
+        st = compare(host_copy(tv), h, f"seed {seed:#x} step {step} tensor_id {tid:#x}")
+        assert st["code_mismatch"] == 0 and st["m_bit_mismatch"] == 0, st
+
+
 def test_short_square_root_and_division_are_correctly_rounded(eco):
     """The step kernels use shorter sequences than sqrtf() and `/` inside stated operand ranges; the library's self-test
     compares short and long form on the device: every fp32 argument of the square root's range (1.6e9 patterns), and
