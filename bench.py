@@ -384,7 +384,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, help="workload number (1-5) of the baseline's configs")
+    ap.add_argument("--config", type=int, default=4, help="workload number: 1-5 = the baseline's configurations; 6 = the shapes of the paper's own SMoE model (Sec. 4.2)")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning: workgroups per compute unit (0 = default)")
     ap.add_argument("--lds-bytes", type=int, default=-1, help="launch tuning: dynamic LDS per workgroup (-1 = default)")
     ap.add_argument("--lds-bytes-wave", type=int, default=-1,

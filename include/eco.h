@@ -57,6 +57,9 @@
  *  - One plan over all tensors of a model is one kernel launch per storage format; per-tensor calls pay a
  *    launch each.
  *  - Tensor lengths that are multiples of 512 keep every tile on the unguarded fast path.
+ *  - Row-wise scale groups (group_size = the row length) of more than 512 elements run with every lane busy when the
+ *    row is a multiple of 512 elements, or when 2, 4 or 8 rows together are (576, 640, 768, 1408, 2304, ...) and the
+ *    tensor has a multiple of that many rows; other lengths leave part of each row's last wave idle.
  */
 #ifndef ECO_H
 #define ECO_H

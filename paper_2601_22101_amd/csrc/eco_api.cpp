@@ -317,8 +317,9 @@ ListOf lists_of(const eco_tensor_t &t, uint64_t gsz, int cls) {
     r.group = gsz;
   } else if (cls == eco::GROUP_WIDE) {
     r.group = gsz < t.numel ? gsz : t.numel;
-    r.units = (t.numel + r.group - 1) / r.group;
-    r.list = L_WIDE1 + static_cast<int>((r.group + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS) - 1;
+    const eco::WideGeometry wg = eco::wide_geometry(t.numel, r.group);
+    r.units = wg.units;
+    r.list = L_WIDE1 + static_cast<int>(wg.waves) - 1;
   } else {
     r.group = t.numel;
     r.units = (t.numel + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS;
@@ -454,8 +455,10 @@ eco_status_t eco_plan_create(const eco_tensor_t *tensors, size_t n, const eco_hp
         if (t.numel % eco::TILE_ELEMS) g.ragged_tensor.push_back(idx);
       } else if (cls == eco::GROUP_WIDE) {
         d.group_size = gsz < t.numel ? gsz : t.numel;
-        units = (t.numel + d.group_size - 1) / d.group_size;
-        list = &g.wide[(d.group_size + eco::TILE_ELEMS - 1) / eco::TILE_ELEMS];
+        const eco::WideGeometry wg = eco::wide_geometry(t.numel, d.group_size);
+        d.slot = wg.rows;
+        units = wg.units;
+        list = &g.wide[wg.waves];
       } else {
         d.group_size = t.numel;
         d.slot = static_cast<uint32_t>(g.tw_tensor.size());
@@ -638,6 +641,7 @@ eco_status_t eco_step_tensors_noalloc(const eco_tensor_t *tensors, size_t n, con
     const bool quantized = t.fmt == ECO_FMT_FP8_E4M3 || t.fmt == ECO_FMT_INT4;
     d.group_size = (cls == eco::GROUP_BLOCK && !quantized) ? hp->block_size : lo.group;
     if (cls == eco::GROUP_BLOCK) d.bs_shift = static_cast<uint32_t>(eco::log2_exact(d.group_size));
+    if (cls == eco::GROUP_WIDE) d.slot = eco::wide_geometry(t.numel, lo.group).rows;
     d.first_unit = fill[t.fmt][lo.list];
     ba.list_pos[k] = start[t.fmt][lo.list] + fill[t.fmt][lo.list];
     ba.units[k] = static_cast<uint32_t>(lo.units);

@@ -51,7 +51,7 @@ struct TensorDesc {          // 80 bytes, device table entry
   uint32_t first_unit;       // index of this tensor's first tile (or first group) in its launch list
   uint32_t tensor_id;
   uint32_t bs_shift;         // log2(group_size) for power-of-two groups of 32..512 elements
-  uint32_t slot;             // tensor-wise scaling: index of the tensor's abs-max slot
+  uint32_t slot;             // tensor-wise scaling: index of the tensor's abs-max slot; wide groups: groups per workgroup
 };
 static_assert(sizeof(TensorDesc) == 80, "TensorDesc layout");
 
@@ -120,6 +120,27 @@ inline bool flat_call_fits(uint64_t numel, uint64_t group_size) {
     threads = (numel + g - 1) / g * 64 * ((g + TILE_ELEMS - 1) / TILE_ELEMS);
   }
   return threads <= MAX_LAUNCH_THREADS;
+}
+// Wide groups (a multiple of 8 up to 8192 elements, not a power of two in [32, 512]): one workgroup of `waves` waves
+// steps `rows` consecutive groups.  One group a workgroup in general; groups of more than 512 elements whose length is
+// not a multiple of 512 leave lanes of their last wave idle, so where 2..8 of them together fill a whole number of
+// waves exactly (1408 = 2.75 waves: four rows in 11 waves; 576: eight rows in 9 waves) and the tensor is a whole number
+// of such bundles, a workgroup takes the bundle.
+struct WideGeometry { uint32_t rows; uint32_t waves; uint64_t units; };
+inline WideGeometry wide_geometry(uint64_t numel, uint64_t g) {          // g = min(group size, numel)
+  const uint64_t ngroups = (numel + g - 1) / g;
+  WideGeometry w = {1u, static_cast<uint32_t>((g + TILE_ELEMS - 1) / TILE_ELEMS), ngroups};
+  if (g > TILE_ELEMS && g % TILE_ELEMS != 0 && numel % g == 0) {
+    for (uint32_t k = 2; k <= 8; ++k) {
+      if ((k * g) % TILE_ELEMS == 0 && k * g / TILE_ELEMS <= MAX_WIDE_WAVES && ngroups % k == 0) {
+        w.rows = k;
+        w.waves = static_cast<uint32_t>(k * g / TILE_ELEMS);
+        w.units = ngroups / k;
+        break;
+      }
+    }
+  }
+  return w;
 }
 inline int log2_exact(uint64_t x) {
   for (int s = 0; s < 64; ++s)

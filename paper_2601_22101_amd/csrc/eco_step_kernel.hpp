@@ -269,6 +269,8 @@ __device__ __forceinline__ bool sqrt_plus_eps8(const float (&x)[8], float eps, f
 // How the abs-max of a scale group is obtained:
 //   RED_BLOCK  the group is 2^shift elements inside one wave: DPP/swizzle all-reduce over its lanes
 //   RED_WG     the group is the whole workgroup (1..16 waves): wave all-reduce, then an LDS combine
+//   RED_WG_ROWS the workgroup holds 2..8 whole groups of more than 512 elements each (a wave meets at most two of
+//              them): per wave one all-reduce for each of its groups, LDS atomic max into the group's entry
 //   RED_ATOMIC first pass of a group larger than a workgroup, one group at a time (the initial quantizer):
 //              wave all-reduce, one atomic max per wave into the group's slot; nothing else is written
 //   RED_TILE   first pass of the step for such groups (tensor-wise scaling): wave all-reduce, the wave's
@@ -276,12 +278,28 @@ __device__ __forceinline__ bool sqrt_plus_eps8(const float (&x)[8], float eps, f
 //              tensor's slot (tens of thousands of atomics on one address serialize in the memory system)
 //   RED_SLOT   second pass: the abs-max is read from that slot; everything is recomputed and written
 //              except the scale (a last, tiny kernel writes it once every tile has used the old one)
-enum : int { RED_BLOCK = 0, RED_WG = 1, RED_ATOMIC = 2, RED_SLOT = 3, RED_TILE = 4 };
+enum : int { RED_BLOCK = 0, RED_WG = 1, RED_ATOMIC = 2, RED_SLOT = 3, RED_TILE = 4, RED_WG_ROWS = 5 };
 
+// arg: RED_BLOCK: log2(group size); RED_WG_ROWS: which of the workgroup's groups the lane belongs to.
 template <int RED>
-__device__ __forceinline__ float group_absmax(float lane_max, int shift, uint32_t *slot) {
-  if (RED == RED_BLOCK) return u2f(group_umax(f2u(lane_max), 1 << (shift - 3)));
+__device__ __forceinline__ float group_absmax(float lane_max, int arg, uint32_t *slot) {
+  if (RED == RED_BLOCK) return u2f(group_umax(f2u(lane_max), 1 << (arg - 3)));
   if (RED == RED_SLOT) return u2f(*slot);
+  if (RED == RED_WG_ROWS) {
+    __shared__ uint32_t row_max[8];
+    if (threadIdx.x < 8) row_max[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t x = f2u(lane_max);
+    const int first = __builtin_amdgcn_readfirstlane(arg), last = __builtin_amdgcn_readlane(arg, 63);
+    const uint32_t m_first = group_umax(arg == first ? x : 0u, 64);
+    if ((threadIdx.x & 63) == 0) atomicMax(&row_max[first], m_first);
+    if (last != first) {                                      // wave-uniform
+      const uint32_t m_last = group_umax(arg == last ? x : 0u, 64);
+      if ((threadIdx.x & 63) == 0) atomicMax(&row_max[last], m_last);
+    }
+    __syncthreads();
+    return u2f(row_max[arg]);
+  }
   const uint32_t wmax = group_umax(f2u(lane_max), 64);
   if (RED == RED_ATOMIC) {
     // the slot only grows, so a wave whose maximum does not exceed what the slot already holds has
@@ -306,10 +324,11 @@ __device__ __forceinline__ float group_absmax(float lane_max, int shift, uint32_
 }
 
 // One lane's 8 consecutive elements, starting at element e0 of tensor td, of which the first nvalid exist;
-// scale group number sg; bs_shift = log2(group size) for RED_BLOCK.
+// scale group number sg; bs_shift = log2(group size) for RED_BLOCK; row = the lane's group within the workgroup for
+// RED_WG_ROWS.
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND, int ACC, int RED>
 __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &td, uint64_t e0, int nvalid,
-                                          uint64_t sg, bool scale_writer, uint32_t *slot) {
+                                          uint64_t sg, bool scale_writer, uint32_t *slot, int row = 0) {
   constexpr bool ADAM = algo_is_adam(ALGO);
   constexpr bool MASTER = algo_is_master(ALGO);
   constexpr bool WRITE = RED != RED_ATOMIC && RED != RED_TILE;   // the first pass of a two-pass group writes nothing
@@ -397,7 +416,7 @@ __device__ __forceinline__ void step_lane(const StepArgs &a, const TensorDesc &t
   }
 
   // ECO_QUANTIZE
-  const float amax = group_absmax<RED>(absmax8(th), (int)td.bs_shift, slot);
+  const float amax = group_absmax<RED>(absmax8(th), RED == RED_WG_ROWS ? row : (int)td.bs_shift, slot);
   if (!WRITE) return;
   if (MASTER) store_f32x8<ACC>(static_cast<float *>(td.aux) + e0, nvalid, th);
   float s_new, inv;
@@ -514,16 +533,28 @@ __global__ __launch_bounds__(WG_THREADS) void eco_step_ragged_kernel(const StepA
 }
 
 // (3) Wide groups (any multiple of 8 up to 8192 elements: row-wise scaling, Sec. 4.1): one workgroup of
-// ceil(group/512) waves per group, abs-max by wave all-reduce plus an LDS combine across the waves.
+// ceil(group/512) waves per group, abs-max by wave all-reduce plus an LDS combine across the waves -- or, where the
+// plan found that 2..8 groups fill a whole number of waves exactly (TensorDesc::slot, see wide_geometry), one
+// workgroup per such bundle of groups, every lane busy.
 template <int FMT, bool STATE_BF16, bool SCALE_BF16, int ALGO, int ROUND>
 __global__ __launch_bounds__(1024) void eco_step_wide_kernel(const StepArgs a) {
   __builtin_amdgcn_s_setprio(3);      // as in eco_step_kernel: loading waves first
   const uint32_t unit = blockIdx.x + a.unit_base;
   const TensorDesc td = load_tensor_desc(a, load_table(a.wide_tensor, unit));
-  const uint64_t grp = unit - td.first_unit;
+  const uint32_t rows = td.slot;
+  const uint64_t grp = (uint64_t)(unit - td.first_unit) * rows;       // the workgroup's first group
   const uint64_t start = grp * td.group_size;
+  const uint32_t lane_elem = threadIdx.x * ELEMS_PER_LANE;
+  const uint64_t e0 = start + lane_elem;
+  if (rows > 1) {
+    const uint32_t gs = (uint32_t)td.group_size;
+    uint32_t row = 0;
+    for (uint32_t k = 1; k < rows; ++k) row += lane_elem >= k * gs ? 1u : 0u;
+    step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED_WG_ROWS>(a, td, e0, 8, grp + row, lane_elem == row * gs, nullptr,
+                                                                               (int)row);
+    return;
+  }
   const uint64_t end = start + td.group_size < td.numel ? start + td.group_size : td.numel;
-  const uint64_t e0 = start + (uint64_t)threadIdx.x * ELEMS_PER_LANE;
   // a group that fills every lane of the workgroup (e.g. rows of 1024, 2048, 4096) needs no per-lane guards
   if (end - start == (uint64_t)blockDim.x * ELEMS_PER_LANE)
     step_lane<FMT, STATE_BF16, SCALE_BF16, ALGO, ROUND, ACC_FULL, RED_WG>(a, td, e0, 8, grp, threadIdx.x == 0, nullptr);

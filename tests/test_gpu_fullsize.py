@@ -158,6 +158,13 @@ def test_config5_row_wise_int4_sampled():
     assert n > 20_000_000
 
 
+def test_config6_paper_shapes_row_wise_sampled():
+    """The paper's own SMoE shapes with its FP8 granularity: rows of 576 and 2304 elements, which the wide-group kernel
+    steps eight and two to a workgroup; unquantized attention, router and embedding in the same plan."""
+    n = run_fullsize(workloads.with_granularity(workloads.config6(), "row"), steps=2, n_tensors=16, seed=19)
+    assert n > 8_000_000          # 1 536 expert matrices x two spans of five rows of 576 or one row of 2304 elements
+
+
 def test_config4_tensor_wise_sampled():
     """One scale per tensor (Sec. 4.4): the two-pass kernels at full size; every sampled tensor is recomputed whole
     (the embedding of 51.5 M elements and the 65 536-element router included)."""

@@ -455,7 +455,9 @@ def wide_group_workload(fmt="fp8", **kw):
     rows from 8 to 8192 elements (1 to 16 waves per group), ragged last rows, one-scale tensors that fit one
     workgroup and ones that need the two-pass kernels (with and without a ragged last tile)."""
     T = workloads.TensorSpec
-    rows = [(5, 1152), (3, 6912), (2, 8192), (7, 520), (9, 96), (4, 1000), (33, 8), (6, 1024), (3, 4096), (2, 5000)]
+    rows = [(5, 1152), (3, 6912), (2, 8192), (7, 520), (9, 96), (4, 1000), (33, 8), (6, 1024), (3, 4096), (2, 5000),
+            # rows of which 2, 4 or 8 fill a whole number of waves: a workgroup takes such a bundle (and 5 rows of 1408 do not)
+            (8, 1408), (16, 576), (6, 768), (4, 640), (12, 2304), (8, 1152), (5, 1408), (2, 7936)]
     ts = [T(f"row{i}", s, fmt, grad_std=1e-3 * (1 + i % 3), granularity="row") for i, s in enumerate(rows)]
     ts.append(T("row_block_mix", (16, 256), fmt, granularity="row"))            # a row that is also a block size
     ts += [T("tw_small", (4096,), fmt, granularity="tensor"), T("tw_8", (8,), fmt, granularity="tensor"),
@@ -640,7 +642,7 @@ def _random_plan(rng, fmt):
     for i in range(int(rng.integers(1, 7))):
         kind = rng.choice(["block", "row", "tensor", "plain"], p=[0.4, 0.3, 0.2, 0.1])
         if kind == "row":
-            cols = int(rng.choice([8, 24, 96, 128, 512, 520, 1000, 1024, 2048, 4096, 4104, 8184, 8192]))
+            cols = int(rng.choice([8, 24, 96, 128, 512, 520, 576, 640, 768, 1000, 1024, 1408, 2048, 2304, 4096, 4104, 8184, 8192]))
             shape = (int(rng.integers(1, 9)), cols)
         else:
             n = int(rng.choice([1, 7, 8, 127, 128, 511, 512, 513, 4095, 4096, 8191, 8192, 8193, 8200, 20000,
