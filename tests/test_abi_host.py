@@ -272,6 +272,19 @@ def test_harness_candidate_orders_use_every_arena_once():
         assert {g for first, g in gaps if not first} == set(range(1, F))
 
 
+def test_launch_geometry_host_checks(tmp_path):
+    """The geometry the library derives from a tensor's scale group (kernel class, rows to a workgroup, what one
+    helper launch holds), compiled for the host alone and checked over every group length: tests/native/geometry_host.cpp."""
+    import subprocess
+    exe = str(tmp_path / "geometry_host")
+    cmd = ["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+           "-I", os.path.join(ROOT, "paper_2601_22101_amd", "csrc"), os.path.join(ROOT, "tests", "native", "geometry_host.cpp"), "-o", exe]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout
+    out = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert out.returncode == 0 and "geometry ok" in out.stdout, out.stdout
+
+
 def test_a_plain_c_client_compiles_links_and_runs(eco, tmp_path):
     """include/eco.h is valid C99 (-Wall -Wextra -pedantic -Werror), libeco.so links by its C names, and the
     host-only entry points give a C caller what they give the Python binding."""
